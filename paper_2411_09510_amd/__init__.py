@@ -1,0 +1,8 @@
+"""mxc — block-quantized communication compression for tensor-parallel partial activations,
+MI355X (gfx950).  Thin Python binding over the C-ABI library ``libmxc.so``; every step of the
+path runs in the library's HIP kernels, PyTorch only provides device memory and streams."""
+from .binding import (Format, MxcError, dequant_reduce, effective_bits, copy_probe, lib,
+                      packed_sizes, quantize, quantize_batched, requantize_chunk, version)
+
+__all__ = ["Format", "MxcError", "dequant_reduce", "effective_bits", "copy_probe", "lib",
+           "packed_sizes", "quantize", "quantize_batched", "requantize_chunk", "version"]

@@ -1,0 +1,207 @@
+"""Argument marshalling for ``libmxc.so`` (same names as the C entry points in include/mxc.h).
+
+Nothing is computed here: tensors are checked for device / dtype / contiguity, outputs are
+allocated with torch, and raw device pointers plus the current HIP stream are handed to the
+library.  There is no fallback: if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmxc.so")
+
+MXC_F32, MXC_BF16 = 0, 1
+
+
+class MxcError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {lib().mxc_strerror(status).decode()} (status {status})")
+
+
+class _CFormat(ctypes.Structure):
+    _fields_ = [("ebits", ctypes.c_int32), ("mbits", ctypes.c_int32),
+                ("block", ctypes.c_int32), ("scale_bits", ctypes.c_int32)]
+
+
+@dataclass(frozen=True)
+class Format:
+    """Element format ExMy, block size and scale format EsM0."""
+    ebits: int
+    mbits: int
+    block: int = 32
+    scale_bits: int = 8
+
+    @property
+    def bits(self) -> int:
+        return 1 + self.ebits + self.mbits
+
+    def c(self) -> _CFormat:
+        return _CFormat(self.ebits, self.mbits, self.block, self.scale_bits)
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load the C-ABI library; builds it first if no built library is present."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            from . import build as _build
+            _build.build()
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+        fp = ctypes.POINTER(_CFormat)
+        szp = ctypes.POINTER(ctypes.c_size_t)
+        L.mxc_strerror.restype = ctypes.c_char_p
+        L.mxc_strerror.argtypes = [ci]
+        L.mxc_version.restype = ctypes.c_char_p
+        L.mxc_version.argtypes = []
+        L.mxc_packed_sizes.restype = ci
+        L.mxc_packed_sizes.argtypes = [fp, i64, i64, szp, szp]
+        L.mxc_effective_bits.restype = ctypes.c_double
+        L.mxc_effective_bits.argtypes = [fp]
+        L.mxc_quantize.restype = ci
+        L.mxc_quantize.argtypes = [fp, vp, i64, i64, vp, vp, vp]
+        L.mxc_quantize_batched.restype = ci
+        L.mxc_quantize_batched.argtypes = [fp, ci, ctypes.POINTER(vp), i64, i64,
+                                           ctypes.POINTER(vp), ctypes.POINTER(vp), vp]
+        L.mxc_dequant_reduce.restype = ci
+        L.mxc_dequant_reduce.argtypes = [fp, ci, ctypes.POINTER(vp), ctypes.POINTER(vp), i64, i64,
+                                         vp, ci, vp]
+        L.mxc_requantize_chunk.restype = ci
+        L.mxc_requantize_chunk.argtypes = [fp, vp, ci, i64, i64, ci, ci, vp, vp, vp]
+        L.mxc_copy_probe.restype = ci
+        L.mxc_copy_probe.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        _lib = L
+    return _lib
+
+
+def version() -> str:
+    return lib().mxc_version().decode()
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        raise MxcError(status, what)
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _dev(t: torch.Tensor, dtype, what: str) -> torch.Tensor:
+    if not t.is_cuda:
+        raise ValueError(f"{what} must be a device tensor")
+    if t.dtype != dtype:
+        raise ValueError(f"{what} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{what} must be contiguous")
+    return t
+
+
+def _ptrs(ts: Sequence[torch.Tensor]):
+    return (ctypes.c_void_p * len(ts))(*[t.data_ptr() for t in ts])
+
+
+def packed_sizes(fmt: Format, tokens: int, hidden: int) -> Tuple[int, int]:
+    cb, sb = ctypes.c_size_t(), ctypes.c_size_t()
+    f = fmt.c()
+    _check(lib().mxc_packed_sizes(ctypes.byref(f), tokens, hidden, ctypes.byref(cb),
+                                  ctypes.byref(sb)), "mxc_packed_sizes")
+    return cb.value, sb.value
+
+
+def effective_bits(fmt: Format) -> float:
+    f = fmt.c()
+    v = lib().mxc_effective_bits(ctypes.byref(f))
+    if v < 0:
+        raise MxcError(-2, "mxc_effective_bits")
+    return v
+
+
+def _alloc_packed(fmt: Format, tokens: int, hidden: int, device):
+    cb, sb = packed_sizes(fmt, tokens, hidden)
+    codes = torch.empty((tokens, cb // tokens if tokens else 0), dtype=torch.uint8, device=device)
+    scales = torch.empty((tokens, sb // tokens if tokens else 0), dtype=torch.uint8, device=device)
+    return codes, scales
+
+
+def quantize(fmt: Format, x: torch.Tensor, codes: Optional[torch.Tensor] = None,
+             scales: Optional[torch.Tensor] = None, stream=None):
+    """bf16 [tokens, hidden] -> (packed codes uint8 [tokens, hidden*b/8], scales uint8
+    [tokens, hidden/block])."""
+    _dev(x, torch.bfloat16, "x")
+    tokens, hidden = x.shape
+    if codes is None or scales is None:
+        codes, scales = _alloc_packed(fmt, tokens, hidden, x.device)
+    f = fmt.c()
+    _check(lib().mxc_quantize(ctypes.byref(f), x.data_ptr(), tokens, hidden, codes.data_ptr(),
+                              scales.data_ptr(), _stream(stream)), "mxc_quantize")
+    return codes, scales
+
+
+def quantize_batched(fmt: Format, xs: Sequence[torch.Tensor],
+                     codes: Optional[List[torch.Tensor]] = None,
+                     scales: Optional[List[torch.Tensor]] = None, stream=None):
+    """The same for several partials of one shape in a single launch."""
+    for x in xs:
+        _dev(x, torch.bfloat16, "x")
+    tokens, hidden = xs[0].shape
+    if codes is None or scales is None:
+        pairs = [_alloc_packed(fmt, tokens, hidden, xs[0].device) for _ in xs]
+        codes, scales = [p[0] for p in pairs], [p[1] for p in pairs]
+    f = fmt.c()
+    _check(lib().mxc_quantize_batched(ctypes.byref(f), len(xs), _ptrs(xs), tokens, hidden,
+                                      _ptrs(codes), _ptrs(scales), _stream(stream)),
+           "mxc_quantize_batched")
+    return codes, scales
+
+
+def dequant_reduce(fmt: Format, codes: Sequence[torch.Tensor], scales: Sequence[torch.Tensor],
+                   tokens: int, hidden: int, out: Optional[torch.Tensor] = None,
+                   out_dtype=torch.float32, stream=None) -> torch.Tensor:
+    """Decode the partials and add them in list order with float32 adds."""
+    for c, s in zip(codes, scales):
+        _dev(c, torch.uint8, "codes")
+        _dev(s, torch.uint8, "scales")
+    if out is None:
+        out = torch.empty((tokens, hidden), dtype=out_dtype, device=codes[0].device)
+    dt = {torch.float32: MXC_F32, torch.bfloat16: MXC_BF16}[out.dtype]
+    f = fmt.c()
+    _check(lib().mxc_dequant_reduce(ctypes.byref(f), len(codes), _ptrs(codes), _ptrs(scales),
+                                    tokens, hidden, out.data_ptr(), dt, _stream(stream)),
+           "mxc_dequant_reduce")
+    return out
+
+
+def requantize_chunk(fmt: Format, reduced: torch.Tensor, tp: int, chunk: int,
+                     codes: Optional[torch.Tensor] = None, scales: Optional[torch.Tensor] = None,
+                     stream=None):
+    """Quantize rows [chunk*tokens/tp, (chunk+1)*tokens/tp) of the reduced tensor."""
+    if reduced.dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError("reduced must be float32 or bfloat16")
+    _dev(reduced, reduced.dtype, "reduced")
+    tokens, hidden = reduced.shape
+    dt = MXC_F32 if reduced.dtype == torch.float32 else MXC_BF16
+    if codes is None or scales is None:
+        codes, scales = _alloc_packed(fmt, tokens // max(tp, 1), hidden, reduced.device)
+    f = fmt.c()
+    _check(lib().mxc_requantize_chunk(ctypes.byref(f), reduced.data_ptr(), dt, tokens, hidden, tp,
+                                      chunk, codes.data_ptr(), scales.data_ptr(),
+                                      _stream(stream)), "mxc_requantize_chunk")
+    return codes, scales
+
+
+def copy_probe(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    nbytes = src.numel() * src.element_size()
+    _check(lib().mxc_copy_probe(dst.data_ptr(), src.data_ptr(), nbytes, _stream(stream)),
+           "mxc_copy_probe")

@@ -1,0 +1,267 @@
+// Host side of the mxc C ABI: argument validation and kernel dispatch.  See include/mxc.h for
+// the contract of every entry point.
+#include "mxc.h"
+
+#include "mxc_kernels.hpp"
+
+namespace {
+
+using namespace mxc;
+
+bool format_ok(const mxc_format *f)
+{
+    if (!f) return false;
+    if (f->ebits < 1 || f->ebits > 3 || f->mbits < 1 || f->mbits > 4) return false;
+    const int b = 1 + f->ebits + f->mbits;
+    if (b < 3 || b > 6) return false;
+    if (f->block != 8 && f->block != 16 && f->block != 32) return false;
+    if (f->scale_bits < 4 || f->scale_bits > 8) return false;
+    return true;
+}
+
+ScaleFmt scale_fmt(const mxc_format *f)
+{
+    ScaleFmt s;
+    s.sbias = (1 << (f->scale_bits - 1)) - 1;
+    s.smax = f->scale_bits == 8 ? 254 : (1 << f->scale_bits) - 1;
+    s.nonfinite = f->scale_bits == 8 ? 255 : s.smax;
+    s.has_nan = f->scale_bits == 8 ? 1 : 0;
+    return s;
+}
+
+// tokens*hidden as a number of 8-element units, or a negative status.
+int shape_units(const mxc_format *f, int64_t tokens, int64_t hidden, size_t *units)
+{
+    if (tokens < 0 || hidden <= 0 || hidden % f->block) return MXC_ERR_SHAPE;
+    if (tokens > 0 && hidden > (int64_t)((1ull << 46) / (uint64_t)tokens)) return MXC_ERR_SHAPE;
+    *units = (size_t)tokens * (size_t)hidden / 8;
+    return MXC_OK;
+}
+
+bool aligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+unsigned grid_for(size_t units)
+{
+    return (unsigned)((units + kUnitsPerGroup - 1) / kUnitsPerGroup);
+}
+
+template <class E, int B, bool SRC32>
+int launch_quantize(const QuantArgs &a, int n, hipStream_t st)
+{
+    hipLaunchKernelGGL((quantize_kernel<E, B, SRC32>), dim3(grid_for(a.units), (unsigned)n),
+                       dim3(kThreads), 0, st, a);
+    return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_HIP;
+}
+
+template <class E, bool SRC32>
+int quantize_by_block(int block, const QuantArgs &a, int n, hipStream_t st)
+{
+    switch (block) {
+    case 8: return launch_quantize<E, 8, SRC32>(a, n, st);
+    case 16: return launch_quantize<E, 16, SRC32>(a, n, st);
+    default: return launch_quantize<E, 32, SRC32>(a, n, st);
+    }
+}
+
+template <bool SRC32>
+int quantize_by_format(const mxc_format *f, const QuantArgs &a, int n, hipStream_t st)
+{
+    switch (f->ebits * 10 + f->mbits) {
+    case 11: return quantize_by_block<Elem<1, 1>, SRC32>(f->block, a, n, st);
+    case 12: return quantize_by_block<Elem<1, 2>, SRC32>(f->block, a, n, st);
+    case 13: return quantize_by_block<Elem<1, 3>, SRC32>(f->block, a, n, st);
+    case 14: return quantize_by_block<Elem<1, 4>, SRC32>(f->block, a, n, st);
+    case 21: return quantize_by_block<Elem<2, 1>, SRC32>(f->block, a, n, st);
+    case 22: return quantize_by_block<Elem<2, 2>, SRC32>(f->block, a, n, st);
+    case 23: return quantize_by_block<Elem<2, 3>, SRC32>(f->block, a, n, st);
+    case 31: return quantize_by_block<Elem<3, 1>, SRC32>(f->block, a, n, st);
+    case 32: return quantize_by_block<Elem<3, 2>, SRC32>(f->block, a, n, st);
+    default: return MXC_ERR_FORMAT;
+    }
+}
+
+template <class E, int B>
+int launch_reduce(const ReduceArgs &a, bool out_bf16, hipStream_t st)
+{
+    if (out_bf16)
+        hipLaunchKernelGGL((dequant_reduce_kernel<E, B, true>), dim3(grid_for(a.units)),
+                           dim3(kThreads), 0, st, a);
+    else
+        hipLaunchKernelGGL((dequant_reduce_kernel<E, B, false>), dim3(grid_for(a.units)),
+                           dim3(kThreads), 0, st, a);
+    return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_HIP;
+}
+
+template <class E>
+int reduce_by_block(int block, const ReduceArgs &a, bool out_bf16, hipStream_t st)
+{
+    switch (block) {
+    case 8: return launch_reduce<E, 8>(a, out_bf16, st);
+    case 16: return launch_reduce<E, 16>(a, out_bf16, st);
+    default: return launch_reduce<E, 32>(a, out_bf16, st);
+    }
+}
+
+int reduce_by_format(const mxc_format *f, const ReduceArgs &a, bool out_bf16, hipStream_t st)
+{
+    switch (f->ebits * 10 + f->mbits) {
+    case 11: return reduce_by_block<Elem<1, 1>>(f->block, a, out_bf16, st);
+    case 12: return reduce_by_block<Elem<1, 2>>(f->block, a, out_bf16, st);
+    case 13: return reduce_by_block<Elem<1, 3>>(f->block, a, out_bf16, st);
+    case 14: return reduce_by_block<Elem<1, 4>>(f->block, a, out_bf16, st);
+    case 21: return reduce_by_block<Elem<2, 1>>(f->block, a, out_bf16, st);
+    case 22: return reduce_by_block<Elem<2, 2>>(f->block, a, out_bf16, st);
+    case 23: return reduce_by_block<Elem<2, 3>>(f->block, a, out_bf16, st);
+    case 31: return reduce_by_block<Elem<3, 1>>(f->block, a, out_bf16, st);
+    case 32: return reduce_by_block<Elem<3, 2>>(f->block, a, out_bf16, st);
+    default: return MXC_ERR_FORMAT;
+    }
+}
+
+int quantize_common(const mxc_format *fmt, int n, const void *const *x, bool src32,
+                    int64_t tokens, int64_t hidden, void *const *codes, void *const *scales,
+                    void *hip_stream)
+{
+    if (!fmt || !x || !codes || !scales) return MXC_ERR_NULL;
+    if (!format_ok(fmt)) return MXC_ERR_FORMAT;
+    if (n < 1 || n > MXC_MAX_TP) return MXC_ERR_TP;
+    QuantArgs a;
+    int rc = shape_units(fmt, tokens, hidden, &a.units);
+    if (rc != MXC_OK) return rc;
+    for (int i = 0; i < n; ++i) {
+        if (!x[i] || !codes[i] || !scales[i]) return MXC_ERR_NULL;
+        if (!aligned(x[i], 16) || !aligned(codes[i], 16) || !aligned(scales[i], 4))
+            return MXC_ERR_ALIGN;
+    }
+    if (a.units == 0) return MXC_OK;
+    for (int i = 0; i < 32; ++i) {
+        const int k = i < n ? i : 0;
+        a.x[i] = x[k];
+        a.codes[i] = codes[k];
+        a.scales[i] = scales[k];
+    }
+    a.sf = scale_fmt(fmt);
+    hipStream_t st = (hipStream_t)hip_stream;
+    return src32 ? quantize_by_format<true>(fmt, a, n, st)
+                 : quantize_by_format<false>(fmt, a, n, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *mxc_strerror(int status)
+{
+    switch (status) {
+    case MXC_OK: return "ok";
+    case MXC_ERR_NULL: return "a required pointer is NULL";
+    case MXC_ERR_FORMAT: return "unsupported element, block or scale format";
+    case MXC_ERR_SHAPE: return "bad shape (non-positive, hidden % block != 0, tokens % tp != 0 or too large)";
+    case MXC_ERR_ALIGN: return "device pointer not aligned (16 bytes for tensors and codes, 4 for scales)";
+    case MXC_ERR_TP: return "tp, chunk or batch count out of range";
+    case MXC_ERR_HIP: return "HIP runtime refused the kernel launch";
+    case MXC_ERR_DTYPE: return "unknown dtype";
+    default: return "unknown mxc status";
+    }
+}
+
+const char *mxc_version(void) { return "mxc 0.1 gfx950"; }
+
+int mxc_packed_sizes(const mxc_format *fmt, int64_t tokens, int64_t hidden, size_t *code_bytes,
+                     size_t *scale_bytes)
+{
+    if (!fmt) return MXC_ERR_NULL;
+    if (!format_ok(fmt)) return MXC_ERR_FORMAT;
+    size_t units;
+    int rc = shape_units(fmt, tokens, hidden, &units);
+    if (rc != MXC_OK) return rc;
+    const size_t b = (size_t)(1 + fmt->ebits + fmt->mbits);
+    if (code_bytes) *code_bytes = units * b;
+    if (scale_bytes) *scale_bytes = units * 8 / (size_t)fmt->block;
+    return MXC_OK;
+}
+
+double mxc_effective_bits(const mxc_format *fmt)
+{
+    if (!format_ok(fmt)) return -1.0;
+    return (double)(1 + fmt->ebits + fmt->mbits) + (double)fmt->scale_bits / (double)fmt->block;
+}
+
+int mxc_quantize(const mxc_format *fmt, const void *x_bf16, int64_t tokens, int64_t hidden,
+                 void *codes, void *scales, void *hip_stream)
+{
+    const void *xs[1] = {x_bf16};
+    void *cs[1] = {codes};
+    void *ss[1] = {scales};
+    return quantize_common(fmt, 1, xs, false, tokens, hidden, cs, ss, hip_stream);
+}
+
+int mxc_quantize_batched(const mxc_format *fmt, int n, const void *const *x_bf16, int64_t tokens,
+                         int64_t hidden, void *const *codes, void *const *scales,
+                         void *hip_stream)
+{
+    return quantize_common(fmt, n, x_bf16, false, tokens, hidden, codes, scales, hip_stream);
+}
+
+int mxc_dequant_reduce(const mxc_format *fmt, int tp, const void *const *codes,
+                       const void *const *scales, int64_t tokens, int64_t hidden, void *out,
+                       int out_dtype, void *hip_stream)
+{
+    if (!fmt || !codes || !scales || !out) return MXC_ERR_NULL;
+    if (!format_ok(fmt)) return MXC_ERR_FORMAT;
+    if (tp < 1 || tp > MXC_MAX_TP) return MXC_ERR_TP;
+    if (out_dtype != MXC_F32 && out_dtype != MXC_BF16) return MXC_ERR_DTYPE;
+    ReduceArgs a;
+    int rc = shape_units(fmt, tokens, hidden, &a.units);
+    if (rc != MXC_OK) return rc;
+    for (int r = 0; r < tp; ++r) {
+        if (!codes[r] || !scales[r]) return MXC_ERR_NULL;
+        if (!aligned(codes[r], 16) || !aligned(scales[r], 4)) return MXC_ERR_ALIGN;
+    }
+    if (!aligned(out, 16)) return MXC_ERR_ALIGN;
+    if (a.units == 0) return MXC_OK;
+    for (int r = 0; r < 32; ++r) {
+        a.codes[r] = codes[r < tp ? r : 0];
+        a.scales[r] = scales[r < tp ? r : 0];
+    }
+    a.out = out;
+    a.tp = tp;
+    a.sf = scale_fmt(fmt);
+    return reduce_by_format(fmt, a, out_dtype == MXC_BF16, (hipStream_t)hip_stream);
+}
+
+int mxc_requantize_chunk(const mxc_format *fmt, const void *reduced, int in_dtype, int64_t tokens,
+                         int64_t hidden, int tp, int chunk, void *codes_chunk, void *scales_chunk,
+                         void *hip_stream)
+{
+    if (!fmt || !reduced || !codes_chunk || !scales_chunk) return MXC_ERR_NULL;
+    if (!format_ok(fmt)) return MXC_ERR_FORMAT;
+    if (in_dtype != MXC_F32 && in_dtype != MXC_BF16) return MXC_ERR_DTYPE;
+    if (tp < 1 || tp > MXC_MAX_TP || chunk < 0 || chunk >= tp) return MXC_ERR_TP;
+    if (tokens < 0 || tokens % tp) return MXC_ERR_SHAPE;
+    size_t units;
+    int rc = shape_units(fmt, tokens, hidden, &units);
+    if (rc != MXC_OK) return rc;
+    const int64_t rows = tokens / tp;
+    const size_t elem = in_dtype == MXC_F32 ? 4 : 2;
+    const char *src = (const char *)reduced + (size_t)chunk * (size_t)rows * (size_t)hidden * elem;
+    const void *xs[1] = {src};
+    void *cs[1] = {codes_chunk};
+    void *ss[1] = {scales_chunk};
+    if (!aligned(reduced, 16)) return MXC_ERR_ALIGN;
+    return quantize_common(fmt, 1, xs, in_dtype == MXC_F32, rows, hidden, cs, ss, hip_stream);
+}
+
+int mxc_copy_probe(void *dst, const void *src, size_t bytes, void *hip_stream)
+{
+    if (!dst || !src) return MXC_ERR_NULL;
+    if (bytes % 16) return MXC_ERR_SHAPE;
+    if (!aligned(dst, 16) || !aligned(src, 16)) return MXC_ERR_ALIGN;
+    if (bytes == 0) return MXC_OK;
+    const size_t n16 = bytes / 16;
+    hipLaunchKernelGGL(copy_kernel, dim3(grid_for(n16)), dim3(kThreads), 0,
+                       (hipStream_t)hip_stream, (u32x4 *)dst, (const u32x4 *)src, n16);
+    return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,99 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every function the header
+declares, and rejects bad arguments on the host before anything is enqueued."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2411_09510_amd as mxc
+    return mxc.lib()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "mxc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mxc_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_functions_are_exported(L):
+    names = declared_functions()
+    assert {"mxc_quantize", "mxc_quantize_batched", "mxc_dequant_reduce", "mxc_requantize_chunk",
+            "mxc_packed_sizes", "mxc_strerror", "mxc_copy_probe"} <= set(names)
+    for n in names:
+        assert getattr(L, n) is not None, n
+
+
+def test_packed_sizes_and_effective_bits(L):
+    import paper_2411_09510_amd as mxc
+    assert mxc.packed_sizes(mxc.Format(2, 1, 32, 8), 4096, 8192) == (16 << 20, 1 << 20)
+    assert mxc.packed_sizes(mxc.Format(2, 2, 32, 8), 4096, 8192) == (20 << 20, 1 << 20)
+    assert mxc.packed_sizes(mxc.Format(3, 2, 16, 8), 4096, 8192) == (24 << 20, 2 << 20)
+    assert mxc.packed_sizes(mxc.Format(2, 1, 32, 8), 0, 8192) == (0, 0)
+    assert mxc.effective_bits(mxc.Format(2, 1, 32, 8)) == 4.25          # Table 3 caption
+    assert mxc.effective_bits(mxc.Format(2, 1, 8, 5)) == 4.625          # Table 1 prints 4.6
+    with pytest.raises(mxc.MxcError):
+        mxc.packed_sizes(mxc.Format(2, 1, 32, 8), 4, 48)                # hidden % block
+    with pytest.raises(mxc.MxcError):
+        mxc.packed_sizes(mxc.Format(4, 1, 32, 8), 4, 64)
+    with pytest.raises(mxc.MxcError):
+        mxc.packed_sizes(mxc.Format(2, 1, 24, 8), 4, 48)
+    with pytest.raises(mxc.MxcError):
+        mxc.packed_sizes(mxc.Format(2, 1, 32, 3), 4, 64)
+    with pytest.raises(mxc.MxcError):
+        mxc.packed_sizes(mxc.Format(3, 4, 32, 8), 4, 64)                # 8 bits > 6
+
+
+def test_host_side_argument_errors(L):
+    """Errors are found before any HIP call, so fake (never dereferenced) pointers are enough."""
+    import paper_2411_09510_amd as mxc
+    from paper_2411_09510_amd.binding import _CFormat
+    f = _CFormat(2, 1, 32, 8)
+    fp = ctypes.byref(f)
+    good, odd = 0x10000, 0x10004
+    vp = ctypes.c_void_p
+    assert L.mxc_quantize(fp, None, 4, 64, good, good, None) == -1
+    assert L.mxc_quantize(None, good, 4, 64, good, good, None) == -1
+    assert L.mxc_quantize(fp, good, 4, 48, good, good, None) == -3
+    assert L.mxc_quantize(fp, good, -1, 64, good, good, None) == -3
+    assert L.mxc_quantize(fp, odd, 4, 64, good, good, None) == -4
+    assert L.mxc_quantize(fp, good, 4, 64, odd, good, None) == -4
+    assert L.mxc_quantize(fp, good, 4, 64, good, 0x10001, None) == -4
+    bad = _CFormat(2, 1, 12, 8)
+    assert L.mxc_quantize(ctypes.byref(bad), good, 4, 64, good, good, None) == -2
+    # empty tensors are fine and launch nothing
+    assert L.mxc_quantize(fp, good, 0, 64, good, good, None) == 0
+    arr = (vp * 2)(good, good)
+    assert L.mxc_quantize_batched(fp, 0, arr, 4, 64, arr, arr, None) == -5
+    assert L.mxc_quantize_batched(fp, 33, arr, 4, 64, arr, arr, None) == -5
+    assert L.mxc_dequant_reduce(fp, 0, arr, arr, 4, 64, good, 0, None) == -5
+    assert L.mxc_dequant_reduce(fp, 33, arr, arr, 4, 64, good, 0, None) == -5
+    assert L.mxc_dequant_reduce(fp, 2, arr, arr, 4, 64, good, 7, None) == -7
+    assert L.mxc_dequant_reduce(fp, 2, arr, arr, 4, 64, None, 0, None) == -1
+    assert L.mxc_dequant_reduce(fp, 2, arr, arr, 4, 64, odd, 0, None) == -4
+    assert L.mxc_dequant_reduce(fp, 2, arr, arr, 0, 64, good, 0, None) == 0
+    nul = (vp * 2)(good, None)
+    assert L.mxc_dequant_reduce(fp, 2, nul, arr, 4, 64, good, 0, None) == -1
+    assert L.mxc_requantize_chunk(fp, good, 0, 6, 64, 4, 0, good, good, None) == -3   # 6 % 4
+    assert L.mxc_requantize_chunk(fp, good, 0, 8, 64, 4, 4, good, good, None) == -5
+    assert L.mxc_requantize_chunk(fp, good, 0, 8, 64, 4, -1, good, good, None) == -5
+    assert L.mxc_requantize_chunk(fp, good, 5, 8, 64, 4, 0, good, good, None) == -7
+    assert L.mxc_copy_probe(good, good, 24, None) == -3
+    assert L.mxc_copy_probe(good, odd, 32, None) == -4
+    assert L.mxc_copy_probe(good, good, 0, None) == 0
+    for code in range(-8, 1):
+        assert L.mxc_strerror(code)
+    assert b"gfx950" in L.mxc_version()
+    assert mxc.version().startswith("mxc")
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    import paper_2411_09510_amd as mxc
+    with pytest.raises(ValueError):
+        mxc.quantize(mxc.Format(2, 1), torch.zeros(4, 64, dtype=torch.bfloat16))

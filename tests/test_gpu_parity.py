@@ -1,0 +1,350 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, element by
+element on the same seeded inputs.  Codes, scales and the float32 reduction are compared
+bit for bit (NaN compared as NaN); the relative-error bar of 1e-6 for the reduction is also
+asserted explicitly."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+HOT = [(2, 1), (2, 2), (3, 2)]
+ALL_ELEMENTS = [(1, 1), (1, 2), (1, 3), (1, 4), (2, 1), (2, 2), (2, 3), (3, 1), (3, 2)]
+
+
+@pytest.fixture(scope="module")
+def mxc():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2411_09510_amd as m
+    m.lib()
+    return m
+
+
+def dev_bf16(bits):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).cuda()
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+def same_f32(a, b):
+    a, b = np.asarray(a, np.float32), np.asarray(b, np.float32)
+    nan_a, nan_b = np.isnan(a), np.isnan(b)
+    return np.array_equal(nan_a, nan_b) and np.array_equal(a.view(np.uint32)[~nan_a],
+                                                            b.view(np.uint32)[~nan_b])
+
+
+def check_quantize(mxc, oracle_mod, x, y, B, bits, s=8):
+    fo = oracle_mod.Format(x, y, B, s)
+    fg = mxc.Format(x, y, B, s)
+    codes, scales = mxc.quantize(fg, dev_bf16(bits))
+    torch.cuda.synchronize()
+    ocodes, oscales = oracle_mod.quantize_bf16(fo, bits)
+    assert np.array_equal(host(scales), oscales), "scales differ"
+    got = oracle_mod.unpack(fo, host(codes), bits.shape[1])
+    if not np.array_equal(got, ocodes):
+        bad = np.argwhere(got != ocodes)[0]
+        raise AssertionError(f"codes differ first at {tuple(bad)}: gpu {got[tuple(bad)]} oracle "
+                             f"{ocodes[tuple(bad)]} input {bits[tuple(bad)]:#06x}")
+    assert np.array_equal(host(codes), oracle_mod.pack(fo, ocodes)), "packing differs"
+    return codes, scales, ocodes, oscales
+
+
+# ------------------------------------------------------------------------ quantize ----------
+
+@pytest.mark.parametrize("x,y", ALL_ELEMENTS)
+@pytest.mark.parametrize("B", [8, 16, 32])
+def test_quantize_config1_all_formats(mxc, oracle_mod, x, y, B):
+    w = workloads.CONFIGS[1]
+    for r in range(w.tp):
+        check_quantize(mxc, oracle_mod, x, y, B, workloads.partial_bf16(w, r))
+
+
+@pytest.mark.parametrize("T,H", [(1, 32), (3, 64), (5, 1056), (7, 8192), (129, 96), (2, 40000 // 32 * 32),
+                                 (1, 8192 + 32), (33, 2048 + 160)])
+def test_quantize_ragged_shapes(mxc, oracle_mod, T, H):
+    """Sizes that end inside a wave's tile, inside a workgroup's tile, and just past one."""
+    w = workloads.Workload("ragged", 1, T, H, seed=17, n_outlier=1, outlier_mult=(30.0, 30.0))
+    bits = workloads.partial_bf16(w, 0)
+    for (x, y) in HOT + [(1, 1)]:
+        for B in (8, 16, 32):
+            check_quantize(mxc, oracle_mod, x, y, B, bits)
+
+
+def test_quantize_does_not_write_past_the_end(mxc, oracle_mod):
+    for (x, y) in HOT + [(1, 1)]:
+        fg = mxc.Format(x, y, 32, 8)
+        T, H = 3, 96
+        cb, sb = mxc.packed_sizes(fg, T, H)
+        codes = torch.full((cb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+        scales = torch.full((sb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+        w = workloads.Workload("canary", 1, T, H, seed=3)
+        xin = dev_bf16(workloads.partial_bf16(w, 0))
+        mxc.quantize(fg, xin, codes[:cb].view(T, -1), scales[:sb].view(T, -1))
+        torch.cuda.synchronize()
+        assert (codes[cb:] == 0xA5).all() and (scales[sb:] == 0xA5).all()
+        ocodes, oscales = oracle_mod.quantize_bf16(oracle_mod.Format(x, y, 32, 8),
+                                                   workloads.partial_bf16(w, 0))
+        assert np.array_equal(host(scales[:sb]).reshape(T, -1), oscales)
+
+
+@pytest.mark.parametrize("x,y", ALL_ELEMENTS)
+def test_quantize_every_bf16_value_every_alignment(mxc, oracle_mod, x, y):
+    """All 65 536 bf16 bit patterns (non-finite ones made finite) beside anchors in many
+    binades: every (value, shared exponent) pair the rounding can see."""
+    B = 32
+    allbits = np.arange(65536, dtype=np.uint32)
+    finite = ((allbits >> 7) & 0xFF) != 0xFF
+    allbits = np.where(finite, allbits, allbits & 0x807F).astype(np.uint16)
+    anchors = [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 40, 126, 127, 128, 129, 130, 133, 200, 247, 250,
+               251, 252, 253, 254]
+    rows = []
+    for ae in anchors:
+        blk = np.zeros((65536 // 16, B), dtype=np.uint16)
+        blk[:, 0] = (ae << 7) | 0x35
+        blk[:, 1:17] = allbits.reshape(-1, 16)
+        blk[:, 17:32] = (allbits.reshape(-1, 16) ^ 0x8000)[:, :15]
+        rows.append(blk)
+    bits = np.concatenate(rows, axis=0)
+    check_quantize(mxc, oracle_mod, x, y, B, bits)
+
+
+@pytest.mark.parametrize("x,y", HOT)
+def test_quantize_edge_tensors(mxc, oracle_mod, x, y):
+    B = 32
+    emax = 2 ** x - 1 - (2 ** (x - 1) - 1)
+    maxval = 2.0 ** emax * (2 - 2.0 ** -y)
+    blocks = []
+    z = np.zeros(B, np.uint16)
+    blocks.append(z.copy())                                   # all +0
+    b = z.copy(); b[::2] = 0x8000; blocks.append(b)           # -0 mixed in
+    b = z.copy(); b[:8] = [0x007F, 0x0040, 0x0020, 0x0010, 0x8030, 0x0001, 0x0050, 0x0060]
+    blocks.append(b)                                          # bf16 subnormals only
+    b = z.copy(); b[0] = 0x7F7F; b[1] = 0xFF7F; b[2] = 0x3F80; blocks.append(b)   # max finite
+    for bad in (0x7F80, 0xFF80, 0x7FC0, 0xFFFF, 0x7F81):      # Inf / NaN anywhere in the block
+        for pos in (0, 13, 31):
+            b = z.copy(); b[:] = 0x3F80; b[pos] = bad; blocks.append(b)
+    near = np.array([maxval, np.nextafter(np.float32(maxval), 0), maxval * 1.01, 2.0 ** (emax + 1) *
+                     (1 - 2.0 ** -8), 2.0 ** emax, 1.0, 0.5, 0.25, 2.0 ** -10], np.float32)
+    b = z.copy(); b[:len(near)] = workloads.f32_to_bf16_bits(near); blocks.append(b)
+    b = z.copy(); b[0] = 0x0080; b[1] = 0x0040; blocks.append(b)          # smallest normal max
+    bits = np.stack(blocks).astype(np.uint16)
+    bits = np.concatenate([bits, bits[::-1]], axis=1)          # two blocks per row
+    check_quantize(mxc, oracle_mod, x, y, B, bits)
+
+
+@pytest.mark.parametrize("s", [4, 5, 6, 7])
+def test_quantize_narrow_scale_formats(mxc, oracle_mod, s):
+    w = workloads.small_like(workloads.CONFIGS[2], 32, 1024)
+    bits = workloads.partial_bf16(w, 0)
+    # stretch some rows far outside the narrow scale range
+    f = workloads.bf16_bits_to_f32(bits)
+    f[1] *= 2.0 ** 40
+    f[2] *= 2.0 ** -40
+    f[3, 5] = np.inf
+    bits = workloads.f32_to_bf16_bits(np.nan_to_num(f, posinf=0, neginf=0))
+    bits[3, 5] = 0x7F80
+    for (x, y) in HOT:
+        check_quantize(mxc, oracle_mod, x, y, 32, bits, s=s)
+
+
+def test_quantize_batched_equals_single(mxc, oracle_mod):
+    w = workloads.small_like(workloads.CONFIGS[3], 24, 2048)
+    xs = [dev_bf16(workloads.partial_bf16(w, r)) for r in range(w.tp)]
+    for (x, y) in HOT:
+        fg = mxc.Format(x, y, 32, 8)
+        cb, sb = mxc.quantize_batched(fg, xs)
+        torch.cuda.synchronize()
+        for r in range(w.tp):
+            c1, s1 = mxc.quantize(fg, xs[r])
+            assert torch.equal(c1, cb[r]) and torch.equal(s1, sb[r])
+            oc, os_ = oracle_mod.quantize_bf16(oracle_mod.Format(x, y, 32, 8),
+                                               workloads.partial_bf16(w, r))
+            assert np.array_equal(host(sb[r]), os_)
+            assert np.array_equal(host(cb[r]), oracle_mod.pack(oracle_mod.Format(x, y, 32, 8), oc))
+
+
+# ------------------------------------------------------------------------ dequant-reduce ----
+
+def oracle_partials(oracle_mod, fo, w):
+    cs, ss = [], []
+    for r in range(w.tp):
+        c, s = oracle_mod.quantize_bf16(fo, workloads.partial_bf16(w, r))
+        cs.append(c)
+        ss.append(s)
+    return cs, ss
+
+
+def check_reduce(mxc, oracle_mod, fo, fg, cs, ss, T, H):
+    packed = [torch.from_numpy(oracle_mod.pack(fo, c)).cuda() for c in cs]
+    scales = [torch.from_numpy(s).cuda() for s in ss]
+    out = mxc.dequant_reduce(fg, packed, scales, T, H)
+    out16 = mxc.dequant_reduce(fg, packed, scales, T, H, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    want = oracle_mod.dequant_reduce(fo, cs, ss)
+    got = host(out)
+    assert same_f32(got, want), "float32 reduction differs"
+    fin = np.isfinite(want)
+    denom = np.abs(want[fin]).max() if fin.any() else 1.0
+    assert np.abs(got[fin].astype(np.float64) - want[fin]).max() <= 1e-6 * max(denom, 1e-30)
+    want16 = oracle_mod.round_to_bf16(want)
+    assert np.array_equal(host(out16.view(torch.int16)).view(np.uint16), want16)
+    return out
+
+
+@pytest.mark.parametrize("x,y", ALL_ELEMENTS)
+@pytest.mark.parametrize("B", [8, 16, 32])
+def test_reduce_config1_all_formats(mxc, oracle_mod, x, y, B):
+    w = workloads.CONFIGS[1]
+    fo, fg = oracle_mod.Format(x, y, B, 8), mxc.Format(x, y, B, 8)
+    cs, ss = oracle_partials(oracle_mod, fo, w)
+    check_reduce(mxc, oracle_mod, fo, fg, cs, ss, w.tokens, w.hidden)
+
+
+@pytest.mark.parametrize("tp", [1, 2, 3, 4, 7, 8, 9, 16, 17, 32])
+def test_reduce_any_tp(mxc, oracle_mod, tp):
+    w = workloads.Workload("tp", tp, 9, 1056, seed=40 + tp, n_outlier=3, outlier_mult=(20.0, 100.0))
+    for (x, y) in HOT:
+        fo, fg = oracle_mod.Format(x, y, 32, 8), mxc.Format(x, y, 32, 8)
+        cs, ss = oracle_partials(oracle_mod, fo, w)
+        check_reduce(mxc, oracle_mod, fo, fg, cs, ss, w.tokens, w.hidden)
+
+
+def test_reduce_arbitrary_codes_and_scales(mxc, oracle_mod):
+    """Random code and scale bytes (not produced by the quantizer): every code, scale bytes 0
+    (binary32-subnormal scale), 254 (products overflow to Inf) and 255 (NaN marker), far-apart
+    binades so that the order of the adds shows."""
+    rng = np.random.default_rng(9)
+    T, H, tp = 6, 2048, 5
+    for (x, y) in ALL_ELEMENTS:
+        for B in (8, 32):
+            fo, fg = oracle_mod.Format(x, y, B, 8), mxc.Format(x, y, B, 8)
+            cs = [rng.integers(0, 2 ** fo.bits, size=(T, H), dtype=np.uint8) for _ in range(tp)]
+            ss = []
+            for r in range(tp):
+                s = rng.integers(100, 160, size=(T, H // B), dtype=np.uint8)
+                s[0] = rng.integers(0, 256, size=H // B)
+                s[1, ::3] = 0
+                s[2, ::5] = 254
+                s[3, ::7] = 255
+                ss.append(s)
+            check_reduce(mxc, oracle_mod, fo, fg, cs, ss, T, H)
+
+
+def test_reduce_keeps_negative_zero_and_order(mxc, oracle_mod):
+    fo, fg = oracle_mod.Format(2, 1, 32, 8), mxc.Format(2, 1, 32, 8)
+    T, H = 1, 64
+    negz = np.full((T, H), 8, np.uint8)
+    s = np.full((T, H // 32), 127, np.uint8)
+    out = check_reduce(mxc, oracle_mod, fo, fg, [negz] * 3, [s] * 3, T, H)
+    assert np.all(np.signbit(host(out)))
+    one = np.full((T, H), 2, np.uint8)
+    big = np.full((T, H // 32), 127 + 24, np.uint8)
+    a = check_reduce(mxc, oracle_mod, fo, fg, [one] * 3, [big, s, s], T, H)
+    b = check_reduce(mxc, oracle_mod, fo, fg, [one] * 3, [s, s, big], T, H)
+    assert float(a[0, 0]) == 2.0 ** 24 and float(b[0, 0]) == 2.0 ** 24 + 2
+
+
+@pytest.mark.parametrize("s", [4, 5, 6, 7])
+def test_reduce_narrow_scale_formats(mxc, oracle_mod, s):
+    w = workloads.small_like(workloads.CONFIGS[2], 16, 512)
+    for (x, y) in HOT:
+        fo, fg = oracle_mod.Format(x, y, 32, s), mxc.Format(x, y, 32, s)
+        cs, ss = oracle_partials(oracle_mod, fo, w)
+        check_reduce(mxc, oracle_mod, fo, fg, cs, ss, w.tokens, w.hidden)
+
+
+# ------------------------------------------------------------------------ requantize --------
+
+@pytest.mark.parametrize("x,y,B", [(2, 1, 16), (2, 1, 32), (2, 2, 32), (3, 2, 32), (1, 3, 8)])
+def test_requantize_chunks(mxc, oracle_mod, x, y, B):
+    w = workloads.small_like(workloads.CONFIGS[4], 64, 1024)
+    fo, fg = oracle_mod.Format(x, y, B, 8), mxc.Format(x, y, B, 8)
+    xs = [dev_bf16(workloads.partial_bf16(w, r)) for r in range(w.tp)]
+    codes, scales = mxc.quantize_batched(fg, xs)
+    red = mxc.dequant_reduce(fg, codes, scales, w.tokens, w.hidden)
+    red16 = mxc.dequant_reduce(fg, codes, scales, w.tokens, w.hidden, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    red_h = host(red)
+    # end to end against the all-oracle pipeline (the reduction is bit-reproducible)
+    ocs, oss = oracle_partials(oracle_mod, fo, w)
+    assert same_f32(red_h, oracle_mod.dequant_reduce(fo, ocs, oss))
+    rows = w.tokens // w.tp
+    for c in range(w.tp):
+        cc, sc = mxc.requantize_chunk(fg, red, w.tp, c)
+        c16, s16 = mxc.requantize_chunk(fg, red16, w.tp, c)
+        torch.cuda.synchronize()
+        oc, os_ = oracle_mod.quantize_f32(fo, red_h[c * rows:(c + 1) * rows])
+        assert np.array_equal(host(sc), os_)
+        assert np.array_equal(host(cc), oracle_mod.pack(fo, oc))
+        bits16 = host(red16.view(torch.int16)).view(np.uint16)[c * rows:(c + 1) * rows]
+        oc, os_ = oracle_mod.quantize_bf16(fo, bits16)
+        assert np.array_equal(host(s16), os_)
+        assert np.array_equal(host(c16), oracle_mod.pack(fo, oc))
+
+
+def test_requantize_f32_rounding_corners(mxc, oracle_mod):
+    """binary32 inputs a hair around rounding midpoints, which need all 24 significand bits."""
+    rng = np.random.default_rng(21)
+    for (x, y) in ALL_ELEMENTS:
+        fo, fg = oracle_mod.Format(x, y, 8, 8), mxc.Format(x, y, 8, 8)
+        book = np.array([oracle_mod.code_value(fo, c) for c in range(2 ** (x + y))])
+        mids = (book[:-1] + book[1:]) / 2
+        rows = []
+        for k in (-126, -100, -20, 0, 3, 60, 120):
+            for mval in mids:
+                base = np.float32(mval * 2.0 ** k)
+                near = [np.nextafter(base, np.float32(0)), base, np.nextafter(base, np.float32(np.inf))]
+                rows.append([np.float32(book[-1] * 2.0 ** k)] + near + [-near[0], -near[2], 0, 0])
+        xin = np.array(rows, dtype=np.float32)
+        rnd = (rng.standard_normal((4096, 8)) * np.exp(rng.standard_normal((4096, 1)) * 20)).astype(np.float32)
+        sub = (rng.standard_normal((256, 8)) * 2.0 ** -140).astype(np.float32)       # subnormals
+        spec = np.zeros((4, 8), np.float32)
+        spec[0, 0] = np.inf; spec[1, 3] = np.nan; spec[2, :] = -0.0; spec[3, 0] = np.finfo(np.float32).max
+        xin = np.concatenate([xin, rnd, sub, spec])
+        pad = (-xin.shape[0]) % 4
+        xin = np.concatenate([xin, np.zeros((pad, 8), np.float32)])
+        t = torch.from_numpy(xin).cuda()
+        cc, sc = mxc.requantize_chunk(fg, t, 1, 0)
+        torch.cuda.synchronize()
+        oc, os_ = oracle_mod.quantize_f32(fo, xin)
+        assert np.array_equal(host(sc), os_)
+        got = oracle_mod.unpack(fo, host(cc), 8)
+        assert np.array_equal(got, oc), np.argwhere(got != oc)[:5]
+
+
+# ------------------------------------------------------------------------ full size ---------
+
+def test_full_size_config3_sampled_rows(mxc, oracle_mod):
+    """The benchmark's launch configuration (all 8 partials of bf16 [4096 x 8192] in one batched
+    launch, then one reduce): rows sampled from every part of the tensor are checked against
+    the oracle; sizes and the untouched remainder via invariants."""
+    w = workloads.CONFIGS[3]
+    rng = np.random.default_rng(1)
+    rows = np.unique(np.concatenate([[0, 1, w.tokens - 1], rng.integers(0, w.tokens, 29)]))
+    parts = [workloads.partial_bf16(w, r) for r in range(w.tp)]
+    xs = [dev_bf16(p) for p in parts]
+    for (x, y, B, s) in w.formats:
+        fo, fg = oracle_mod.Format(x, y, B, s), mxc.Format(x, y, B, s)
+        codes, scales = mxc.quantize_batched(fg, xs)
+        out = mxc.dequant_reduce(fg, codes, scales, w.tokens, w.hidden)
+        torch.cuda.synchronize()
+        ocs, oss = [], []
+        for r in range(w.tp):
+            oc, os_ = oracle_mod.quantize_bf16(fo, parts[r][rows])
+            assert np.array_equal(host(scales[r])[rows], os_)
+            assert np.array_equal(host(codes[r])[rows], oracle_mod.pack(fo, oc))
+            ocs.append(oc)
+            oss.append(os_)
+            # scale rule holds everywhere: byte = max biased exponent of the block - emax
+            expf = ((parts[r] >> 7) & 0xFF).reshape(w.tokens, -1, B).max(axis=2).astype(np.int64)
+            emax = 2 ** x - 1 - (2 ** (x - 1) - 1)
+            assert np.array_equal(host(scales[r]), np.maximum(expf - emax, 0).astype(np.uint8))
+        want = oracle_mod.dequant_reduce(fo, ocs, oss)
+        assert same_f32(host(out)[rows], want)
+        cb, sb = mxc.packed_sizes(fg, w.tokens, w.hidden)
+        ratio = w.tokens * w.hidden * 2 / (cb + sb)
+        assert abs(ratio - 16 / (fo.bits + s / B)) < 1e-9
