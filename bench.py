@@ -1,0 +1,257 @@
+#!/usr/bin/env python3
+"""Benchmark of the compression hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic input at the
+Llama-70B-shaped configuration: the 8 tensor-parallel partials (bf16 [4096 x 8192] each) are
+block-quantized in one batched launch, and 8 compressed partials are decoded and summed to
+float32 by one launch.  The metric is GB/s of bf16 activations processed per step (the
+512 MiB of partials that go through both kernels) with all inputs resident in HBM.
+
+So that no kernel reads data another kernel has just left in the 256 MB last-level cache, the
+packed buffers rotate over three sets (a step quantizes into one set and reduces the set that
+was written two steps earlier) and the bf16 inputs alternate between two copies.
+
+Prints ONE JSON line; see the design doc for the fields `roofline` and `cpu_baseline`.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=3, help="workload number (1..5)")
+    ap.add_argument("--format", default="e2m1", help="element format of the timed step, e.g. e2m1")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the untimed format sweep")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=0, help="rows per partial for the oracle timing")
+    return ap.parse_args()
+
+
+def parse_format(s):
+    s = s.lower()
+    return int(s[1]), int(s[3])
+
+
+def algorithmic_bytes(fmt, tp, tokens, hidden):
+    """Bytes the method itself must move, per launch: (quantize, dequant-reduce)."""
+    n = tokens * hidden
+    packed = n * fmt.bits / 8 + n * 1 / fmt.block          # codes + one scale byte per block
+    return tp * (n * 2 + packed), tp * packed + n * 4
+
+
+def read_traffic(workload, kernel, fmt_name):
+    """HBM traffic per launch measured with rocprofv3 --pmc (committed under profiles/)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    key = f"{workload}.{kernel}.{fmt_name}"
+    for line in open(path):
+        line = line.strip()
+        if line.startswith("#") or "=" not in line:
+            continue
+        k, v = [t.strip() for t in line.split("=", 1)]
+        if k == key:
+            return float(v.split()[0])
+    return None
+
+
+def cpu_baseline(w, x, y, host_parts, rows):
+    """The oracle, as it is, on a bounded sample of the same workload (host cores)."""
+    import oracle
+    fo = oracle.Format(x, y, 32, 8)
+    oracle.lib()
+    parts = [np.ascontiguousarray(p[:rows]) for p in host_parts]
+    t0 = time.perf_counter()
+    cs, ss = [], []
+    for p in parts:
+        c, s = oracle.quantize_bf16(fo, p)
+        cs.append(c)
+        ss.append(s)
+    t1 = time.perf_counter()
+    oracle.dequant_reduce(fo, cs, ss)
+    t2 = time.perf_counter()
+    nbytes = w.tp * rows * w.hidden * 2
+    return {
+        "value": nbytes / (t2 - t0) / 1e9, "unit": "GB/s", "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": f"first {rows} of {w.tokens} rows of each of the {w.tp} partials of the timed "
+                  f"workload, quantize + dequant-reduce, e{x}m{y} block 32",
+        "quantize_GBps": nbytes / (t1 - t0) / 1e9, "dequant_reduce_GBps": nbytes / (t2 - t1) / 1e9,
+        "seconds": t2 - t0,
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no second GPU); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2411_09510_amd as mxc
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    mxc.lib()
+    torch.cuda.set_device(0)
+    w = workloads.CONFIGS[args.config]
+    x, y = parse_format(args.format)
+    fmt = mxc.Format(x, y, 32, 8)
+    T, H, N = w.tokens, w.hidden, w.tp
+    stream = torch.cuda.current_stream()
+
+    # ---- inputs, resident in HBM -----------------------------------------------------------
+    host_parts = [workloads.partial_bf16(w, r) for r in range(N)]
+    def upload():
+        return [torch.from_numpy(p.view(np.int16)).view(torch.bfloat16).cuda() for p in host_parts]
+    x_sets = [upload(), upload()]
+    R = 3
+    def packed_set(f):
+        cb, sb = mxc.packed_sizes(f, T, H)
+        return ([torch.empty((T, cb // T), dtype=torch.uint8, device="cuda") for _ in range(N)],
+                [torch.empty((T, sb // T), dtype=torch.uint8, device="cuda") for _ in range(N)])
+    sets = [packed_set(fmt) for _ in range(R)]
+    outs = [torch.empty((T, H), dtype=torch.float32, device="cuda") for _ in range(2)]
+
+    def step(i, f, psets, ev=None):
+        cq, sq = psets[i % R]
+        cr, sr = psets[(i + 1) % R]
+        if ev: ev[0].record(stream)
+        mxc.quantize_batched(f, x_sets[i % 2], cq, sq)
+        if ev: ev[1].record(stream)
+        mxc.dequant_reduce(f, cr, sr, T, H, out=outs[i % 2])
+        if ev: ev[2].record(stream)
+
+    for i in range(R):                      # fill every packed set before anything is reduced
+        mxc.quantize_batched(fmt, x_sets[0], *sets[i])
+    for i in range(args.warmup):
+        step(i, fmt, sets)
+    torch.cuda.synchronize()
+
+    # ---- timed region ----------------------------------------------------------------------
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, fmt, sets, events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    q_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    r_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+
+    bf16_bytes = N * T * H * 2
+    q_bytes, r_bytes = algorithmic_bytes(fmt, N, T, H)
+    value = bf16_bytes / (ms_per_step * 1e-3) / 1e9
+    fname = f"e{x}m{y}"
+
+    def roof(kernel, nbytes, ms):
+        ach = nbytes / (ms * 1e-3) / 1e9
+        return {"kernel": kernel, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                "traffic": read_traffic(w.name, kernel, fname),
+                "algorithmic_bytes_per_launch": nbytes, "avg_launch_ms": ms}
+
+    rq, rr = roof("quantize_kernel", q_bytes, q_ms), roof("dequant_reduce_kernel", r_bytes, r_ms)
+    dominant = rq if q_ms >= r_ms else rr
+
+    result = {
+        "metric": "quantize + dequant-reduce GB/s of bf16 activations processed, 1x MI355X",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16 in, u8 codes, f32 accumulate", "data": "synthetic",
+        "config": {"workload": w.name, "tp": N, "tokens": T, "hidden": H, "element": fname,
+                   "block": 32, "scale": "e8m0",
+                   "compression_ratio": 16 / mxc.effective_bits(fmt)},
+        "roofline": dominant,
+        "kernels": {
+            "quantize": {"GBps_bf16": bf16_bytes / (q_ms * 1e-3) / 1e9, **rq},
+            "dequant_reduce": {"GBps_bf16": bf16_bytes / (r_ms * 1e-3) / 1e9, **rr},
+        },
+    }
+
+    # ---- untimed extras: copy ceiling and the other element formats of the configuration ----
+    if not args.no_sweep:
+        def time_calls(fn, n=20, warm=3):
+            for i in range(warm):
+                fn(i)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record(stream)
+            for i in range(n):
+                fn(i)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n
+        src = [torch.empty(512 << 20, dtype=torch.uint8, device="cuda") for _ in range(2)]
+        dst = [torch.empty(512 << 20, dtype=torch.uint8, device="cuda") for _ in range(2)]
+        for s in src:
+            s.zero_()
+        cms = time_calls(lambda i: mxc.copy_probe(dst[i % 2], src[i % 2]))
+        copy_gbs = 2 * (512 << 20) / (cms * 1e-3) / 1e9
+        result["copy_ceiling"] = {"GBps": copy_gbs, "frac_of_peak": copy_gbs / HBM_PEAK_GBS,
+                                  "bytes_moved": 2 * (512 << 20)}
+        del src, dst
+        sweep = {}
+        for (fx, fy, fb, fs) in w.formats:
+            f = mxc.Format(fx, fy, fb, fs)
+            ps = [packed_set(f) for _ in range(R)]
+            for i in range(R):
+                mxc.quantize_batched(f, x_sets[0], *ps[i])
+            qb, rb = algorithmic_bytes(f, N, T, H)
+            qms = time_calls(lambda i: mxc.quantize_batched(f, x_sets[i % 2], *ps[i % R]))
+            rms = time_calls(lambda i: mxc.dequant_reduce(f, *ps[i % R], T, H, out=outs[i % 2]))
+            sweep[f"e{fx}m{fy}_b{fb}"] = {
+                "compression_ratio": 16 / mxc.effective_bits(f),
+                "quantize": {"ms": qms, "GBps_bf16": bf16_bytes / qms / 1e6,
+                             "hbm_GBps": qb / qms / 1e6, "frac": qb / qms / 1e6 / HBM_PEAK_GBS,
+                             "frac_of_copy": qb / qms / 1e6 / copy_gbs},
+                "dequant_reduce": {"ms": rms, "GBps_bf16": bf16_bytes / rms / 1e6,
+                                   "hbm_GBps": rb / rms / 1e6, "frac": rb / rms / 1e6 / HBM_PEAK_GBS,
+                                   "frac_of_copy": rb / rms / 1e6 / copy_gbs},
+            }
+            del ps
+        if w.requantize:
+            f = mxc.Format(*w.formats[-1])
+            red = outs[0]
+            cb, sb = mxc.packed_sizes(f, T // N, H)
+            cc = [torch.empty(cb, dtype=torch.uint8, device="cuda") for _ in range(N)]
+            sc = [torch.empty(sb, dtype=torch.uint8, device="cuda") for _ in range(N)]
+            def requant_all(i):
+                for c in range(N):
+                    mxc.requantize_chunk(f, red, N, c, cc[c], sc[c])
+            ms = time_calls(requant_all)
+            nb = T * H * 4 + N * (cb + sb)
+            sweep["requantize_all_chunks"] = {"ms": ms, "hbm_GBps": nb / ms / 1e6,
+                                              "frac": nb / ms / 1e6 / HBM_PEAK_GBS}
+        result["sweep"] = sweep
+
+    if not args.no_cpu_baseline:
+        rows = args.cpu_rows or min(T, 4096)
+        result["cpu_baseline"] = cpu_baseline(w, x, y, host_parts, rows)
+    else:
+        result["cpu_baseline"] = None
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -40,16 +40,27 @@ int shape_units(const mxc_format *f, int64_t tokens, int64_t hidden, size_t *uni
 
 bool aligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
-unsigned grid_for(size_t units)
+// Launch shapes, chosen by measurement on MI355X (HBM-bound kernels: more, smaller waves and
+// nontemporal loads stream best).
+constexpr int kQuantU = 4;          // units per lane, quantize
+constexpr bool kQuantNTL = false, kQuantNTS = false;
+constexpr int kReduceU = 4;         // units per lane, dequant-reduce
+constexpr int kReduceRC = 8;        // ranks loaded together
+constexpr bool kReduceNTL = false, kReduceNTS = false;
+constexpr int kCopyU = 1;
+constexpr bool kHw = true;          // use the scaled-conversion instructions where exact
+
+unsigned grid_for(size_t units, int per_lane)
 {
-    return (unsigned)((units + kUnitsPerGroup - 1) / kUnitsPerGroup);
+    const size_t per_group = (size_t)kThreads * (size_t)per_lane;
+    return (unsigned)((units + per_group - 1) / per_group);
 }
 
 template <class E, int B, bool SRC32>
 int launch_quantize(const QuantArgs &a, int n, hipStream_t st)
 {
-    hipLaunchKernelGGL((quantize_kernel<E, B, SRC32>), dim3(grid_for(a.units), (unsigned)n),
-                       dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL((quantize_kernel<E, B, SRC32, kQuantU, kQuantNTL, kQuantNTS, kHw>),
+                       dim3(grid_for(a.units, kQuantU), (unsigned)n), dim3(kThreads), 0, st, a);
     return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_HIP;
 }
 
@@ -83,12 +94,15 @@ int quantize_by_format(const mxc_format *f, const QuantArgs &a, int n, hipStream
 template <class E, int B>
 int launch_reduce(const ReduceArgs &a, bool out_bf16, hipStream_t st)
 {
+    const dim3 grid(grid_for(a.units, kReduceU));
     if (out_bf16)
-        hipLaunchKernelGGL((dequant_reduce_kernel<E, B, true>), dim3(grid_for(a.units)),
-                           dim3(kThreads), 0, st, a);
+        hipLaunchKernelGGL((dequant_reduce_kernel<E, B, true, kReduceU, kReduceRC, kReduceNTL,
+                                                  kReduceNTS, kHw>),
+                           grid, dim3(kThreads), 0, st, a);
     else
-        hipLaunchKernelGGL((dequant_reduce_kernel<E, B, false>), dim3(grid_for(a.units)),
-                           dim3(kThreads), 0, st, a);
+        hipLaunchKernelGGL((dequant_reduce_kernel<E, B, false, kReduceU, kReduceRC, kReduceNTL,
+                                                  kReduceNTS, kHw>),
+                           grid, dim3(kThreads), 0, st, a);
     return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_HIP;
 }
 
@@ -259,8 +273,8 @@ int mxc_copy_probe(void *dst, const void *src, size_t bytes, void *hip_stream)
     if (!aligned(dst, 16) || !aligned(src, 16)) return MXC_ERR_ALIGN;
     if (bytes == 0) return MXC_OK;
     const size_t n16 = bytes / 16;
-    hipLaunchKernelGGL(copy_kernel, dim3(grid_for(n16)), dim3(kThreads), 0,
-                       (hipStream_t)hip_stream, (u32x4 *)dst, (const u32x4 *)src, n16);
+    hipLaunchKernelGGL((copy_kernel<kCopyU, false>), dim3(grid_for(n16, kCopyU)), dim3(kThreads),
+                       0, (hipStream_t)hip_stream, (u32x4 *)dst, (const u32x4 *)src, n16);
     return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_HIP;
 }
 

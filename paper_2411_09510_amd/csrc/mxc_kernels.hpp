@@ -5,9 +5,16 @@
 // back, so the flat view of inputs, packed codes and scales is exact).  A "unit" is 8 consecutive
 // elements: one 128-bit load of bf16, one dword of 4-bit codes, b bytes of b-bit codes.  A block of
 // B elements is B/8 neighbouring lanes of one wave (1, 2 or 4 lanes), so the block maximum is a
-// quad-local DPP reduction and never touches LDS.  Each wave owns kUnitsPerLane * 64 consecutive
-// units; in step u lane l handles unit (wave_base + u*64 + l), which keeps every load and store
-// instruction contiguous across the wave.
+// quad-local DPP reduction and never touches LDS.  Each wave owns U * 64 consecutive units; in
+// step u lane l handles unit (wave_base + u*64 + l), which keeps every load and store instruction
+// contiguous across the wave.
+//
+// Element rounding and decoding use the gfx950 scaled-conversion instructions wherever the
+// element format maps onto a hardware format bit for bit (checked exhaustively against the CPU
+// oracle): E2M1 is the hardware FP4; a format with 2 (3) mantissa bits is the low part of the
+// code space of BF8 = E5M2 (FP8 = E4M3) once the block scale is shifted so that the smallest
+// normals coincide.  Everything else, and every block whose scale leaves the range in which that
+// shift is representable, takes the integer path below, which is exact for every input.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -16,13 +23,15 @@
 namespace mxc {
 
 constexpr int kThreads = 256;        // 4 waves per workgroup
-constexpr int kUnitsPerLane = 4;     // 16-byte units per lane and tile
-constexpr int kUnitsPerWave = 64 * kUnitsPerLane;
-constexpr int kUnitsPerGroup = kThreads * kUnitsPerLane;
 
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+typedef short i16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+enum HwKind { HW_NONE = 0, HW_FP4 = 1, HW_BF8 = 2, HW_FP8 = 3 };
 
 // Element format ExMy (Method, parameter list): facts derived at compile time.
 template <int X, int Y>
@@ -32,6 +41,11 @@ struct Elem {
     static constexpr int beta = (1 << (X - 1)) - 1;
     static constexpr int emax = (1 << X) - 1 - beta;
     static constexpr uint32_t magmask = (1u << (X + Y)) - 1u;
+    // hardware format whose code space contains this one
+    static constexpr int hw = (X == 2 && Y == 1) ? HW_FP4 : (Y == 2) ? HW_BF8 : (Y == 3) ? HW_FP8
+                                                                                       : HW_NONE;
+    // exponent bias of that hardware format
+    static constexpr int hw_bias = hw == HW_BF8 ? 15 : hw == HW_FP8 ? 7 : beta;
 };
 
 // Scale format EsM0, runtime (s only changes two clamps per block).
@@ -56,6 +70,29 @@ __device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
     return __builtin_bit_cast(uint32_t, r);
 }
 
+// Two bfloat16 in a dword, as the vector type the conversion builtins take.  The argument is a
+// by-value scalar on purpose: bit-casting an element of a vector variable in place made the
+// compiler read element 0 for every index.
+__device__ __forceinline__ bf16x2 as_bf16x2(uint32_t pair)
+{
+    bf16x2 r;
+    __builtin_memcpy(&r, &pair, sizeof(r));
+    return r;
+}
+
+template <bool NT, class T>
+__device__ __forceinline__ T ld(const T *p)
+{
+    return NT ? __builtin_nontemporal_load(p) : *p;
+}
+
+template <bool NT, class T>
+__device__ __forceinline__ void st(T *p, T v)
+{
+    if (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
 // Maximum over the B/8 lanes that share a block.
 template <int B>
 __device__ __forceinline__ uint32_t block_max(uint32_t m)
@@ -65,18 +102,9 @@ __device__ __forceinline__ uint32_t block_max(uint32_t m)
     return m;
 }
 
-// Scale byte from the block maximum's biased binary32/bfloat16 exponent field (0..255):
-// floor(log2 max) - emax + sbias, clamped; 255 in the exponent field means Inf/NaN.
-template <class E>
-__device__ __forceinline__ int scale_code(int max_expfield, const ScaleFmt &sf)
-{
-    int c = max_expfield - 127 - E::emax + sf.sbias;
-    c = min(max(c, 0), sf.smax);
-    return max_expfield == 255 ? sf.nonfinite : c;
-}
-
 // ---------------------------------------------------------------------------------------------
-// Rounding of one element to an ExMy magnitude code, ties to the even code, saturating.
+// Integer-path rounding of one element to an ExMy magnitude code, ties to the even code,
+// saturating.
 //
 // round_small_sig: for inputs with at most 8 significant bits (bfloat16).  The value is scaled
 // by 2^(beta-127-e) so that the element format's smallest normal lands on binary32's smallest
@@ -113,17 +141,36 @@ __device__ __forceinline__ uint32_t round_full_sig(float v, int neg_e)
 }
 
 // ---------------------------------------------------------------------------------------------
+// Four b-bit codes <-> four bytes of a dword (code k in byte k).
+template <int BITS>
+__device__ __forceinline__ uint32_t squeeze4(uint32_t bytes)
+{
+    constexpr uint32_t m1 = (1u << BITS) - 1u, m2 = (1u << 2 * BITS) - 1u;
+    // bytes 0,1 -> 2b bits in the low half, bytes 2,3 -> 2b bits in the high half
+    uint32_t t = (bytes & (m1 * 0x00010001u)) | ((bytes >> (8 - BITS)) & ((m1 << BITS) * 0x00010001u));
+    return (t & m2) | ((t >> (16 - 2 * BITS)) & (m2 << 2 * BITS));
+}
+
+template <int BITS>
+__device__ __forceinline__ uint32_t spread4(uint32_t fields)
+{
+    constexpr uint32_t m1 = (1u << BITS) - 1u, m2 = (1u << 2 * BITS) - 1u;
+    uint32_t t = (fields & m2) | ((fields << (16 - 2 * BITS)) & (m2 << 16));
+    return (t & (m1 * 0x00010001u)) | ((t << (8 - BITS)) & (m1 * 0x01000100u));
+}
+
+// ---------------------------------------------------------------------------------------------
 // Moving b-bit codes between "8 codes per lane" and the packed little-endian bit stream.
 // A quad of lanes owns 32 codes = b dwords of the stream, at dword index quad*b.
 
 // Store: lane holds its 8 codes in the low 8b bits of v.
-template <int BITS>
+template <int BITS, bool NT>
 __device__ __forceinline__ void store_codes(uint32_t *codes, size_t unit, uint64_t v, bool valid)
 {
     const int i = (int)(threadIdx.x & 3);
     uint32_t *q = codes + (unit >> 2) * BITS;
     if (BITS == 4) {
-        if (valid) codes[unit] = (uint32_t)v;
+        if (valid) st<NT>(codes + unit, (uint32_t)v);
     } else if (BITS == 5) {
         // lane i's 40 bits start at stream bit 40i = dword i, bit 8i
         uint64_t w = v << (8 * i);
@@ -131,8 +178,8 @@ __device__ __forceinline__ void store_codes(uint32_t *codes, size_t unit, uint64
         uint32_t from_prev = dpp<quad_perm(3, 0, 1, 2)>(hi);     // lane i gets hi of lane i-1
         uint32_t d = lo | (i ? from_prev : 0u);
         if (valid) {
-            q[i] = d;
-            if (i == 0) q[4] = from_prev;                        // hi of lane 3
+            st<NT>(q + i, d);
+            if (i == 0) st<NT>(q + 4, from_prev);                // hi of lane 3
         }
     } else if (BITS == 6) {
         // pairs of lanes own 3 dwords: even lane bits 0..47, odd lane bits 48..95
@@ -143,10 +190,10 @@ __device__ __forceinline__ void store_codes(uint32_t *codes, size_t unit, uint64
         uint32_t *p = q + 3 * (i >> 1);
         if (valid) {
             if (i & 1) {
-                p[1] = lo | got;
-                p[2] = hi;
+                st<NT>(p + 1, lo | got);
+                st<NT>(p + 2, hi);
             } else {
-                p[0] = lo;
+                st<NT>(p, lo);
             }
         }
     } else {  // BITS == 3: lane i's 24 bits start at stream bit 24i
@@ -155,23 +202,23 @@ __device__ __forceinline__ void store_codes(uint32_t *codes, size_t unit, uint64
         uint32_t lo = (uint32_t)w, hi = (uint32_t)(w >> 32);
         uint32_t from_next = dpp<quad_perm(1, 2, 3, 3)>(lo);      // lane i gets lo of lane i+1
         uint32_t d = (i ? hi : lo) | from_next;
-        if (valid && i < 3) q[i] = d;
+        if (valid && i < 3) st<NT>(q + i, d);
     }
 }
 
 // Load: returns the lane's 8 codes in the low 8b bits.
-template <int BITS>
+template <int BITS, bool NT>
 __device__ __forceinline__ uint64_t load_codes(const uint32_t *codes, size_t unit, bool valid)
 {
     const int i = (int)(threadIdx.x & 3);
     const uint32_t *q = codes + (unit >> 2) * BITS;
     if (BITS == 4) {
-        return valid ? codes[unit] : 0u;
+        return valid ? ld<NT>(codes + unit) : 0u;
     } else if (BITS == 5) {
         uint32_t d = 0, extra = 0;
         if (valid) {
-            d = q[i];
-            if (i == 0) extra = q[4];
+            d = ld<NT>(q + i);
+            if (i == 0) extra = ld<NT>(q + 4);
         }
         uint32_t give = i ? d : extra;
         uint32_t next = dpp<quad_perm(1, 2, 3, 0)>(give);         // lane i gets dword i+1
@@ -182,10 +229,10 @@ __device__ __forceinline__ uint64_t load_codes(const uint32_t *codes, size_t uni
         uint32_t a = 0, b = 0;
         if (valid) {
             if (i & 1) {
-                a = p[1];
-                b = p[2];
+                a = ld<NT>(p + 1);
+                b = ld<NT>(p + 2);
             } else {
-                a = p[0];
+                a = ld<NT>(p);
             }
         }
         uint32_t other = dpp<quad_perm(1, 0, 3, 2)>(a);           // even lane gets dword 1
@@ -194,7 +241,7 @@ __device__ __forceinline__ uint64_t load_codes(const uint32_t *codes, size_t uni
         return (i & 1) ? odd : even;
     } else {  // BITS == 3
         uint32_t d = 0;
-        if (valid && i < 3) d = q[i];
+        if (valid && i < 3) d = ld<NT>(q + i);
         uint32_t prev = dpp<quad_perm(0, 0, 1, 2)>(d);            // lane i gets dword i-1
         uint64_t w = ((uint64_t)d << 32) | prev;
         return (w >> (32 - 8 * i)) & 0xFFFFFFull;
@@ -212,89 +259,181 @@ struct QuantArgs {
     ScaleFmt sf;
 };
 
+// Eight elements -> packed codes, integer path.  w: the unit's raw input dwords.
+template <class E, bool SRC32>
+__device__ __forceinline__ uint64_t encode_unit_generic(const u32x4 (&w)[SRC32 ? 2 : 1], int neg_e)
+{
+    uint64_t packed = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        uint32_t mag, bits;
+        if (SRC32) {
+            bits = w[j >> 2][j & 3];
+            mag = round_full_sig<E>(__uint_as_float(bits), neg_e);
+        } else {
+            const uint32_t pair = w[0][j >> 1];
+            bits = (j & 1) ? (pair & 0xFFFF0000u) : (pair << 16);
+            mag = round_small_sig<E>(__uint_as_float(bits), neg_e + E::beta - 127);
+        }
+        const uint32_t code = mag | ((bits >> 31) << (E::x + E::y));
+        packed |= (uint64_t)code << (j * E::bits);
+    }
+    return packed;
+}
+
+// Scaled conversions need their byte / word selector as a literal: one wrapper per selector.
+template <int K, bool SRC32, int NW>
+__device__ __forceinline__ uint32_t cvt_pair_to_fp4(uint32_t old, const u32x4 (&w)[NW], float s)
+{
+    if (SRC32)
+        return __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(old, __uint_as_float(w[K >> 1][2 * (K & 1)]),
+                                                        __uint_as_float(w[K >> 1][2 * (K & 1) + 1]), s, K);
+    else
+        return __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(old, as_bf16x2(w[0][K]), s, K);
+}
+
+// Element pair P (0..3) of the unit -> two bytes in word (P & 1) of `old`.
+template <int HWK, int P, bool SRC32, int NW>
+__device__ __forceinline__ i16x2 cvt_pair_to_8bit(i16x2 old, const u32x4 (&w)[NW], float s)
+{
+    constexpr bool hi = (P & 1) != 0;
+    if (SRC32) {
+        const float a = __uint_as_float(w[P >> 1][2 * (P & 1)]);
+        const float b = __uint_as_float(w[P >> 1][2 * (P & 1) + 1]);
+        return HWK == HW_BF8 ? __builtin_amdgcn_cvt_scalef32_pk_bf8_f32(old, a, b, s, hi)
+                             : __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(old, a, b, s, hi);
+    } else {
+        const bf16x2 v = as_bf16x2(w[0][P]);
+        return HWK == HW_BF8 ? __builtin_amdgcn_cvt_scalef32_pk_bf8_bf16(old, v, s, hi)
+                             : __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(old, v, s, hi);
+    }
+}
+
+// Four bytes sign<<7 | magnitude (magnitude <= magmask + 1) -> four b-bit codes, squeezed.
+template <class E>
+__device__ __forceinline__ uint32_t bytes_to_codes(uint32_t v)
+{
+    // the scale rule keeps |p| below 2^(emax+1); rounding can reach exactly that value, whose
+    // code is magmask+1: fold it back onto the largest magnitude
+    v -= (v >> (E::x + E::y)) & 0x01010101u;
+    // sign from bit 7 down to bit x+y
+    v = (v & (E::magmask * 0x01010101u)) |
+        ((v >> (7 - E::x - E::y)) & ((E::magmask + 1u) * 0x01010101u));
+    return squeeze4<E::bits>(v);
+}
+
+// Eight elements -> packed codes with the scaled-conversion instructions.  hw_scale is the
+// binary32 whose exponent field is the power of two the inputs are divided by.
+template <class E, bool SRC32>
+__device__ __forceinline__ uint64_t encode_unit_hw(const u32x4 (&w)[SRC32 ? 2 : 1], float hw_scale)
+{
+    constexpr int NW = SRC32 ? 2 : 1;
+    if (E::hw == HW_FP4) {
+        uint32_t r = 0;
+        r = cvt_pair_to_fp4<0, SRC32, NW>(r, w, hw_scale);
+        r = cvt_pair_to_fp4<1, SRC32, NW>(r, w, hw_scale);
+        r = cvt_pair_to_fp4<2, SRC32, NW>(r, w, hw_scale);
+        r = cvt_pair_to_fp4<3, SRC32, NW>(r, w, hw_scale);
+        return r;
+    } else {
+        constexpr int K = E::hw == HW_BF8 ? HW_BF8 : HW_FP8;
+        i16x2 lo = {0, 0}, hi = {0, 0};
+        lo = cvt_pair_to_8bit<K, 0, SRC32, NW>(lo, w, hw_scale);
+        lo = cvt_pair_to_8bit<K, 1, SRC32, NW>(lo, w, hw_scale);
+        hi = cvt_pair_to_8bit<K, 2, SRC32, NW>(hi, w, hw_scale);
+        hi = cvt_pair_to_8bit<K, 3, SRC32, NW>(hi, w, hw_scale);
+        const uint32_t c0 = bytes_to_codes<E>(__builtin_bit_cast(uint32_t, lo));
+        const uint32_t c1 = bytes_to_codes<E>(__builtin_bit_cast(uint32_t, hi));
+        return (uint64_t)c0 | ((uint64_t)c1 << (4 * E::bits));
+    }
+}
+
 // SRC32 = false: bfloat16 input, one 128-bit load per unit.
 // SRC32 = true : binary32 input, two 128-bit loads per unit.
-template <class E, int B, bool SRC32>
+// U: units per lane.  NTL/NTS: nontemporal loads / stores.  HW: use scaled conversions.
+template <class E, int B, bool SRC32, int U, bool NTL, bool NTS, bool HW>
 __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantArgs a)
 {
     constexpr int G = B / 8;                     // lanes per block
+    constexpr int NW = SRC32 ? 2 : 1;
+    constexpr bool kHw = HW && E::hw != HW_NONE;
     const int lane = (int)(threadIdx.x & 63);
     const int wave = (int)(threadIdx.x >> 6);
     const size_t wave_base =
-        ((size_t)blockIdx.x * (kThreads / 64) + (size_t)wave) * (size_t)kUnitsPerWave;
+        ((size_t)blockIdx.x * (kThreads / 64) + (size_t)wave) * (size_t)(U * 64);
     const void *xin = a.x[blockIdx.y];
     uint32_t *codes = (uint32_t *)a.codes[blockIdx.y];
     uint8_t *scales = (uint8_t *)a.scales[blockIdx.y];
     const ScaleFmt sf = a.sf;
 
-    u32x4 w[kUnitsPerLane][SRC32 ? 2 : 1];
-    bool valid[kUnitsPerLane];
+    u32x4 w[U][NW];
+    bool valid[U];
 #pragma unroll
-    for (int u = 0; u < kUnitsPerLane; ++u) {
+    for (int u = 0; u < U; ++u) {
         const size_t unit = wave_base + (size_t)(u * 64 + lane);
         valid[u] = unit < a.units;
         const u32x4 zero = {0u, 0u, 0u, 0u};
-        if (SRC32) {
-            const u32x4 *p = (const u32x4 *)xin + unit * 2;
-            w[u][0] = valid[u] ? p[0] : zero;
-            w[u][SRC32 ? 1 : 0] = valid[u] ? p[1] : zero;
-        } else {
-            w[u][0] = valid[u] ? ((const u32x4 *)xin)[unit] : zero;
-        }
+#pragma unroll
+        for (int h = 0; h < NW; ++h)
+            w[u][h] = valid[u] ? ld<NTL>((const u32x4 *)xin + unit * NW + h) : zero;
     }
 
     int my_scale = 0;                            // the scale byte this lane will store
 #pragma unroll
-    for (int u = 0; u < kUnitsPerLane; ++u) {
+    for (int u = 0; u < U; ++u) {
         const size_t unit = wave_base + (size_t)(u * 64 + lane);
-        int expfield;
+        int expfield;                            // biased exponent field of the block maximum
         if (SRC32) {
             uint32_t m = 0;
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+            for (int h = 0; h < NW; ++h)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) m = max(m, w[u][h][j] & 0x7FFFFFFFu);
-            m = block_max<B>(m);
-            expfield = (int)(m >> 23);
+            expfield = (int)(block_max<B>(m) >> 23);
         } else {
             const u32x4 v = w[u][0];
             uint32_t m = pk_max_u16(pk_max_u16(v.x & 0x7FFF7FFFu, v.y & 0x7FFF7FFFu),
                                     pk_max_u16(v.z & 0x7FFF7FFFu, v.w & 0x7FFF7FFFu));
             m = max(m & 0xFFFFu, m >> 16);
-            m = block_max<B>(m);
-            expfield = (int)(m >> 7);
+            expfield = (int)(block_max<B>(m) >> 7);
         }
-        const int sc = scale_code<E>(expfield, sf);
+        // shared exponent: floor(log2 max) - emax, as a scale code, clamped to the scale format
+        const int unclamped = expfield - 127 - E::emax + sf.sbias;
         const bool finite = expfield != 255;
-        const int neg_e = sf.sbias - sc;         // -e
+        const int sc = finite ? min(max(unclamped, 0), sf.smax) : sf.nonfinite;
+        const int e = sc - sf.sbias;
 
-        uint64_t packed = 0;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            uint32_t mag, sign;
-            if (SRC32) {
-                const uint32_t bits = w[u][j >> 2][j & 3];
-                mag = round_full_sig<E>(__uint_as_float(bits), neg_e);
-                sign = bits >> 31;
+        uint64_t packed;
+        if (kHw) {
+            // divide by 2^(e - beta + hw_bias): the element format's smallest normal then falls
+            // on the hardware format's smallest normal.  Usable while that power of two has a
+            // binary32 exponent field and (for the 8-bit formats) the scale's upper clamp is
+            // idle, which is what bounds |p| below 2^(emax+1).
+            const int field = e - E::beta + E::hw_bias + 127;
+            const bool ok = field >= 0 && field <= 254 && (E::hw == HW_FP4 || unclamped <= sf.smax);
+            if (__builtin_amdgcn_ballot_w64(!ok && finite) == 0) {
+                packed = encode_unit_hw<E, SRC32>(w[u], __uint_as_float((uint32_t)max(field, 0) << 23));
             } else {
-                const uint32_t pair = w[u][0][j >> 1];
-                const uint32_t bits = (j & 1) ? (pair & 0xFFFF0000u) : (pair << 16);
-                mag = round_small_sig<E>(__uint_as_float(bits), neg_e + E::beta - 127);
-                sign = bits >> 31;
+                packed = encode_unit_generic<E, SRC32>(w[u], -e);
             }
-            const uint32_t code = finite ? (mag | (sign << (E::x + E::y))) : 0u;
-            packed |= (uint64_t)code << (j * E::bits);
+        } else {
+            packed = encode_unit_generic<E, SRC32>(w[u], -e);
         }
-        store_codes<E::bits>(codes, unit, packed, valid[u]);
+        if (!finite) packed = 0;
+        store_codes<E::bits, NTS>(codes, unit, packed, valid[u]);
 
-        // Every lane of a block knows the block's scale.  Over G consecutive steps lane l keeps
-        // the scale of step (l % G); after the G-th step each lane stores one byte, so that the
-        // wave writes 64 consecutive scale bytes with one instruction.
-        if ((lane & (G - 1)) == (u & (G - 1))) my_scale = sc;
-        if ((u & (G - 1)) == G - 1) {
-            const int step = u - (G - 1) + (lane & (G - 1));
-            const size_t first_unit = wave_base + (size_t)(step * 64 + (lane / G) * G);
-            if (first_unit < a.units) scales[first_unit / G] = (uint8_t)my_scale;
+        // Every lane of a block knows the block's scale.
+        if (U % G == 0) {
+            // Over G consecutive steps lane l keeps the scale of step (l % G); after the G-th
+            // step each lane stores one byte, so the wave writes 64 consecutive scale bytes.
+            if ((lane & (G - 1)) == (u & (G - 1))) my_scale = sc;
+            if ((u & (G - 1)) == G - 1) {
+                const int step = u - (G - 1) + (lane & (G - 1));
+                const size_t first_unit = wave_base + (size_t)(step * 64 + (lane / G) * G);
+                if (first_unit < a.units) scales[first_unit / G] = (uint8_t)my_scale;
+            }
+        } else {
+            if ((lane & (G - 1)) == 0 && valid[u]) scales[unit / G] = (uint8_t)sc;
         }
     }
 }
@@ -311,15 +450,60 @@ struct ReduceArgs {
     ScaleFmt sf;
 };
 
-// Decode code j of `v` to binary32 times 2^k (exact): the magnitude code, shifted so that its
-// mantissa sits at the top of binary32's fraction field, is value * 2^(beta-127) as a (possibly
-// subnormal) binary32; ldexp moves it to value * 2^e.
+// Integer-path decode of code j of `v` to binary32 times 2^k (exact): the magnitude code,
+// shifted so that its mantissa sits at the top of binary32's fraction field, is
+// value * 2^(beta-127) as a (possibly subnormal) binary32; ldexp moves it to value * 2^e.
 template <class E>
 __device__ __forceinline__ float decode(uint64_t v, int j, int k /* e + 127 - beta */)
 {
     const uint32_t c = (uint32_t)(v >> (j * E::bits));
     const uint32_t bits = ((c & E::magmask) << (23 - E::y)) | ((c >> (E::x + E::y)) << 31);
     return ldexpf(__uint_as_float(bits), k);
+}
+
+template <int K>
+__device__ __forceinline__ f32x2 cvt_fp4_pair(uint32_t v, float s)
+{
+    return __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(v, s, K);
+}
+
+template <int HWK, bool HI>
+__device__ __forceinline__ f32x2 cvt_8bit_pair(uint32_t v, float s)
+{
+    return HWK == HW_BF8 ? __builtin_amdgcn_cvt_scalef32_pk_f32_bf8(v, s, HI)
+                         : __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(v, s, HI);
+}
+
+// Four squeezed b-bit codes -> four bytes sign<<7 | magnitude.
+template <class E>
+__device__ __forceinline__ uint32_t codes_to_bytes(uint32_t f)
+{
+    uint32_t b = spread4<E::bits>(f);
+    return (b & (E::magmask * 0x01010101u)) | ((b << (7 - E::x - E::y)) & 0x80808080u);
+}
+
+// Eight codes -> eight binary32 values times the power of two in hw_scale's exponent field.
+template <class E>
+__device__ __forceinline__ void decode_unit_hw(uint64_t v, float hw_scale, float (&d)[8])
+{
+    f32x2 r0, r1, r2, r3;
+    if (E::hw == HW_FP4) {
+        r0 = cvt_fp4_pair<0>((uint32_t)v, hw_scale);
+        r1 = cvt_fp4_pair<1>((uint32_t)v, hw_scale);
+        r2 = cvt_fp4_pair<2>((uint32_t)v, hw_scale);
+        r3 = cvt_fp4_pair<3>((uint32_t)v, hw_scale);
+    } else {
+        constexpr int K = E::hw == HW_BF8 ? HW_BF8 : HW_FP8;
+        constexpr uint32_t m4 = (1u << 4 * E::bits) - 1u;
+        const uint32_t b0 = codes_to_bytes<E>((uint32_t)v & m4);
+        const uint32_t b1 = codes_to_bytes<E>((uint32_t)(v >> (4 * E::bits)) & m4);
+        r0 = cvt_8bit_pair<K, false>(b0, hw_scale);
+        r1 = cvt_8bit_pair<K, true>(b0, hw_scale);
+        r2 = cvt_8bit_pair<K, false>(b1, hw_scale);
+        r3 = cvt_8bit_pair<K, true>(b1, hw_scale);
+    }
+    d[0] = r0.x; d[1] = r0.y; d[2] = r1.x; d[3] = r1.y;
+    d[4] = r2.x; d[5] = r2.y; d[6] = r3.x; d[7] = r3.y;
 }
 
 __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f)
@@ -329,18 +513,20 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f)
     return (f != f) ? 0x7FC0u : r;
 }
 
-template <class E, int B, bool OUT_BF16>
+// RC: ranks whose loads are issued together.
+template <class E, int B, bool OUT_BF16, int U, int RC, bool NTL, bool NTS, bool HW>
 __global__ __launch_bounds__(kThreads) void dequant_reduce_kernel(ReduceArgs a)
 {
     constexpr int G = B / 8;
-    constexpr int RC = 8;                        // ranks loaded together
+    constexpr bool kHw = HW && E::hw != HW_NONE;
     const int lane = (int)(threadIdx.x & 63);
     const int wave = (int)(threadIdx.x >> 6);
     const size_t wave_base =
-        ((size_t)blockIdx.x * (kThreads / 64) + (size_t)wave) * (size_t)kUnitsPerWave;
+        ((size_t)blockIdx.x * (kThreads / 64) + (size_t)wave) * (size_t)(U * 64);
     const ScaleFmt sf = a.sf;
 
-    for (int u = 0; u < kUnitsPerLane; ++u) {
+#pragma unroll 1
+    for (int u = 0; u < U; ++u) {
         const size_t unit = wave_base + (size_t)(u * 64 + lane);
         const bool valid = unit < a.units;
         float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -352,19 +538,28 @@ __global__ __launch_bounds__(kThreads) void dequant_reduce_kernel(ReduceArgs a)
             for (int i = 0; i < RC; ++i) {
                 const bool on = valid && (r0 + i < a.tp);
                 const int r = min(r0 + i, a.tp - 1);
-                v[i] = load_codes<E::bits>((const uint32_t *)a.codes[r], unit, on);
-                sc[i] = on ? (int)((const uint8_t *)a.scales[r])[unit / G] : 0;
+                v[i] = load_codes<E::bits, NTL>((const uint32_t *)a.codes[r], unit, on);
+                sc[i] = on ? (int)ld<NTL>((const uint8_t *)a.scales[r] + unit / G) : sf.sbias;
             }
 #pragma unroll
             for (int i = 0; i < RC; ++i) {
                 if (r0 + i < a.tp) {
-                    const int k = sc[i] - sf.sbias + 127 - E::beta;
-                    poisoned = poisoned || (sf.has_nan && sc[i] == 255);
+                    const int e = sc[i] - sf.sbias;
+                    const bool marker = sf.has_nan && sc[i] == 255;
+                    poisoned = poisoned || marker;
+                    float d[8];
+                    // the hardware format reads the code as value * 2^(beta - hw_bias), so
+                    // multiply by 2^(e - beta + hw_bias): usable while it has an exponent field
+                    const int field = e - E::beta + E::hw_bias + 127;
+                    const bool ok = field >= 0 && field <= 254;
+                    if (kHw && __builtin_amdgcn_ballot_w64(!ok) == 0) {
+                        decode_unit_hw<E>(v[i], __uint_as_float((uint32_t)field << 23), d);
+                    } else {
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        const float d = decode<E>(v[i], j, k);
-                        acc[j] = (r0 + i == 0) ? d : acc[j] + d;
+                        for (int j = 0; j < 8; ++j) d[j] = decode<E>(v[i], j, e + 127 - E::beta);
                     }
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) acc[j] = (r0 + i == 0) ? d[j] : acc[j] + d[j];
                 }
             }
         }
@@ -378,11 +573,11 @@ __global__ __launch_bounds__(kThreads) void dequant_reduce_kernel(ReduceArgs a)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
                     o[j] = f32_to_bf16_rne(acc[2 * j]) | (f32_to_bf16_rne(acc[2 * j + 1]) << 16);
-                ((u32x4 *)a.out)[unit] = o;
+                st<NTS>((u32x4 *)a.out + unit, o);
             } else {
                 f32x4 *o = (f32x4 *)a.out + unit * 2;
-                o[0] = f32x4{acc[0], acc[1], acc[2], acc[3]};
-                o[1] = f32x4{acc[4], acc[5], acc[6], acc[7]};
+                st<NTS>(o, f32x4{acc[0], acc[1], acc[2], acc[3]});
+                st<NTS>(o + 1, f32x4{acc[4], acc[5], acc[6], acc[7]});
             }
         }
     }
@@ -390,19 +585,20 @@ __global__ __launch_bounds__(kThreads) void dequant_reduce_kernel(ReduceArgs a)
 
 // ---------------------------------------------------------------------------------------------
 // Plain 128-bit copy, the practical bandwidth ceiling the codec kernels are compared with.
+template <int U, bool NT>
 __global__ __launch_bounds__(kThreads) void copy_kernel(u32x4 *dst, const u32x4 *src, size_t n16)
 {
-    const size_t base = (size_t)blockIdx.x * (size_t)kUnitsPerGroup + threadIdx.x;
-    u32x4 v[kUnitsPerLane];
+    const size_t base = (size_t)blockIdx.x * (size_t)(kThreads * U) + threadIdx.x;
+    u32x4 v[U];
 #pragma unroll
-    for (int u = 0; u < kUnitsPerLane; ++u) {
+    for (int u = 0; u < U; ++u) {
         const size_t i = base + (size_t)u * kThreads;
-        if (i < n16) v[u] = src[i];
+        if (i < n16) v[u] = ld<NT>(src + i);
     }
 #pragma unroll
-    for (int u = 0; u < kUnitsPerLane; ++u) {
+    for (int u = 0; u < U; ++u) {
         const size_t i = base + (size_t)u * kThreads;
-        if (i < n16) dst[i] = v[u];
+        if (i < n16) st<NT>(dst + i, v[u]);
     }
 }
 
