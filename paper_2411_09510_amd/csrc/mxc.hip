@@ -42,11 +42,11 @@ bool aligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
 // Launch shapes, chosen by measurement on MI355X (HBM-bound kernels: more, smaller waves and
 // nontemporal loads stream best).
-constexpr int kQuantU = 4;          // units per lane, quantize
-constexpr bool kQuantNTL = false, kQuantNTS = false;
+constexpr int kQuantU = 2;          // units per lane, quantize
+constexpr bool kQuantNTL = true, kQuantNTS = false;
 constexpr int kReduceU = 4;         // units per lane, dequant-reduce
 constexpr int kReduceRC = 8;        // ranks loaded together
-constexpr bool kReduceNTL = false, kReduceNTS = false;
+constexpr bool kReduceNTL = true, kReduceNTS = true;
 constexpr int kCopyU = 1;
 constexpr bool kHw = true;          // use the scaled-conversion instructions where exact
 
@@ -94,15 +94,30 @@ int quantize_by_format(const mxc_format *f, const QuantArgs &a, int n, hipStream
 template <class E, int B>
 int launch_reduce(const ReduceArgs &a, bool out_bf16, hipStream_t st)
 {
-    const dim3 grid(grid_for(a.units, kReduceU));
-    if (out_bf16)
-        hipLaunchKernelGGL((dequant_reduce_kernel<E, B, true, kReduceU, kReduceRC, kReduceNTL,
-                                                  kReduceNTS, kHw>),
-                           grid, dim3(kThreads), 0, st, a);
-    else
-        hipLaunchKernelGGL((dequant_reduce_kernel<E, B, false, kReduceU, kReduceRC, kReduceNTL,
-                                                  kReduceNTS, kHw>),
-                           grid, dim3(kThreads), 0, st, a);
+    if (a.units % 4 == 0) {
+        // whole 32-element chunks: one lane per chunk, output staged through LDS
+        const size_t chunks = a.units / 4;
+        const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads));
+        if (out_bf16)
+            hipLaunchKernelGGL((dequant_reduce_tile_kernel<E, B, true, kReduceRC, kReduceNTL,
+                                                           kReduceNTS, kHw>),
+                               grid, dim3(kThreads), 0, st, a);
+        else
+            hipLaunchKernelGGL((dequant_reduce_tile_kernel<E, B, false, kReduceRC, kReduceNTL,
+                                                           kReduceNTS, kHw>),
+                               grid, dim3(kThreads), 0, st, a);
+    } else {
+        // sizes that are not a multiple of 32 elements (only possible with blocks of 8 or 16)
+        const dim3 grid(grid_for(a.units, kReduceU));
+        if (out_bf16)
+            hipLaunchKernelGGL((dequant_reduce_kernel<E, B, true, kReduceU, kReduceRC, kReduceNTL,
+                                                      kReduceNTS, kHw>),
+                               grid, dim3(kThreads), 0, st, a);
+        else
+            hipLaunchKernelGGL((dequant_reduce_kernel<E, B, false, kReduceU, kReduceRC, kReduceNTL,
+                                                      kReduceNTS, kHw>),
+                               grid, dim3(kThreads), 0, st, a);
+    }
     return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_HIP;
 }
 

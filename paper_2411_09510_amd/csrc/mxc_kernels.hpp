@@ -583,6 +583,169 @@ __global__ __launch_bounds__(kThreads) void dequant_reduce_kernel(ReduceArgs a)
     }
 }
 
+// LEN bits starting at bit `pos` of a little-endian stream held in NW dwords.  Callers pass
+// positions that are constants after unrolling, so this folds to one or two instructions.
+template <int NW>
+__device__ __forceinline__ uint32_t stream_bits_rt(const uint32_t (&s)[NW], int pos, int len)
+{
+    const int wd = pos >> 5, off = pos & 31;
+    const uint32_t mask = len >= 32 ? 0xFFFFFFFFu : ((1u << len) - 1u);
+    uint32_t v = s[wd] >> off;
+    if (off + len > 32) v |= s[wd + 1 < NW ? wd + 1 : wd] << (32 - off);
+    return v & mask;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Dequantize + reduce, tile form: the fast path for tensors whose size is a multiple of 32.
+//
+// Each lane owns a "chunk" of 32 consecutive elements (one block of 32, two of 16, four of 8): its
+// codes are 4b contiguous bytes per rank (a single 128-bit load for 4-bit codes), its scales 1, 2
+// or 4 contiguous bytes per rank, so every load instruction of the wave is contiguous and as wide
+// as the format allows.  The lane's 32 sums are then exchanged through a wave-private LDS tile so
+// that the wave writes its 8 KiB (4 KiB for bf16) of output as contiguous 128-bit stores.
+
+template <class E, int B, bool OUT_BF16, int RC, bool NTL, bool NTS, bool HW>
+__global__ __launch_bounds__(kThreads) void dequant_reduce_tile_kernel(ReduceArgs a)
+{
+    constexpr int NB = 32 / B;                   // blocks (scales) per chunk
+    constexpr int W = E::bits;                   // dwords of codes per chunk
+    constexpr bool kHw = HW && E::hw != HW_NONE;
+    constexpr int OC = OUT_BF16 ? 4 : 8;         // 16-byte output pieces per lane
+    __shared__ u32x4 tile[kThreads / 64][64 * OC];
+
+    const int lane = (int)(threadIdx.x & 63);
+    const int wave = (int)(threadIdx.x >> 6);
+    const size_t wave_chunk0 = ((size_t)blockIdx.x * (kThreads / 64) + (size_t)wave) * 64;
+    const size_t chunk = wave_chunk0 + (size_t)lane;
+    const size_t nchunks = a.units / 4;
+    const bool valid = chunk < nchunks;
+    const ScaleFmt sf = a.sf;
+
+    float acc[32];
+#pragma unroll
+    for (int j = 0; j < 32; ++j) acc[j] = 0.f;
+    bool poisoned[NB];
+#pragma unroll
+    for (int n = 0; n < NB; ++n) poisoned[n] = false;
+
+    for (int r0 = 0; r0 < a.tp; r0 += RC) {
+        uint32_t cw[RC][W];
+        uint32_t sw[RC];
+#pragma unroll
+        for (int i = 0; i < RC; ++i) {
+            const bool on = valid && (r0 + i < a.tp);
+            const int r = min(r0 + i, a.tp - 1);
+            const uint32_t *cp = (const uint32_t *)a.codes[r] + chunk * W;
+#pragma unroll
+            for (int k = 0; k < W; ++k) cw[i][k] = 0u;
+            if (on) {
+                if (W == 4) {
+                    const u32x4 v = ld<NTL>((const u32x4 *)cp);
+                    cw[i][0] = v.x; cw[i][1] = v.y; cw[i][2] = v.z; cw[i][3 < W ? 3 : 0] = v.w;
+                } else if (W == 6) {
+                    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+                    for (int k = 0; k < 3; ++k) {
+                        const u32x2 v = ld<NTL>((const u32x2 *)cp + k);
+                        cw[i][(2 * k) < W ? 2 * k : 0] = v.x;
+                        cw[i][(2 * k + 1) < W ? 2 * k + 1 : 0] = v.y;
+                    }
+                } else {
+#pragma unroll
+                    for (int k = 0; k < W; ++k) cw[i][k] = ld<NTL>(cp + k);
+                }
+            }
+            // NB scale bytes, little-endian in one register; idle lanes read as "e = 0"
+            uint32_t sb = (uint32_t)sf.sbias * 0x01010101u;
+            if (on) {
+                const uint8_t *sp = (const uint8_t *)a.scales[r] + chunk * NB;
+                if (NB == 1) sb = ld<NTL>(sp);
+                else if (NB == 2) sb = ld<NTL>((const uint16_t *)sp);
+                else sb = ld<NTL>((const uint32_t *)sp);
+            }
+            sw[i] = sb;
+        }
+#pragma unroll
+        for (int i = 0; i < RC; ++i) {
+            if (r0 + i < a.tp) {
+#pragma unroll
+                for (int n = 0; n < NB; ++n) {
+                    const int sc = (int)((sw[i] >> (8 * n)) & 0xFFu);
+                    const int e = sc - sf.sbias;
+                    poisoned[n] = poisoned[n] || (sf.has_nan && sc == 255);
+                    const int field = e - E::beta + E::hw_bias + 127;
+                    const bool ok = field >= 0 && field <= 254;
+                    float d[B];
+                    if (kHw && __builtin_amdgcn_ballot_w64(!ok) == 0) {
+                        const float hs = __uint_as_float((uint32_t)field << 23);
+                        // B codes of block n, eight at a time
+#pragma unroll
+                        for (int g = 0; g < B / 8; ++g) {
+                            // the 8 codes occupy 8b bits starting at bit first*b (positions
+                            // are constants once n and g are unrolled)
+                            const int first = n * B + g * 8;
+                            const uint32_t lo = stream_bits_rt<W>(cw[i], first * W, 4 * W);
+                            const uint32_t hi = stream_bits_rt<W>(cw[i], first * W + 4 * W, 4 * W);
+                            const uint64_t v8 = (uint64_t)lo | ((uint64_t)hi << (4 * W));
+                            float d8[8];
+                            decode_unit_hw<E>(v8, hs, d8);
+#pragma unroll
+                            for (int j = 0; j < 8; ++j) d[g * 8 + j] = d8[j];
+                        }
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < B; ++j) {
+                            const uint32_t c = stream_bits_rt<W>(cw[i], (n * B + j) * W, W);
+                            const uint32_t bits = ((c & E::magmask) << (23 - E::y)) |
+                                                  ((c >> (E::x + E::y)) << 31);
+                            d[j] = ldexpf(__uint_as_float(bits), e + 127 - E::beta);
+                        }
+                    }
+#pragma unroll
+                    for (int j = 0; j < B; ++j)
+                        acc[n * B + j] = (r0 + i == 0) ? d[j] : acc[n * B + j] + d[j];
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int n = 0; n < NB; ++n)
+        if (poisoned[n]) {
+#pragma unroll
+            for (int j = 0; j < B; ++j) acc[n * B + j] = __uint_as_float(0x7FC00000u);
+        }
+
+    // Exchange through LDS.  Lane l owns output pieces l*OC .. l*OC+OC-1 of the wave's tile; piece
+    // c is written to slot (c + l) % OC of the lane's row so that both the row-wise writes and
+    // the piece-wise reads spread over all banks.
+    u32x4 *t = tile[wave];
+#pragma unroll
+    for (int c = 0; c < OC; ++c) {
+        u32x4 v;
+        if (OUT_BF16) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                v[j] = f32_to_bf16_rne(acc[8 * c + 2 * j]) | (f32_to_bf16_rne(acc[8 * c + 2 * j + 1]) << 16);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = __float_as_uint(acc[4 * c + j]);
+        }
+        t[lane * OC + ((c + lane) & (OC - 1))] = v;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    u32x4 *out = (u32x4 *)a.out + wave_chunk0 * OC;
+    const size_t pieces_left = wave_chunk0 < nchunks ? (nchunks - wave_chunk0) * OC : 0;
+#pragma unroll
+    for (int r = 0; r < OC; ++r) {
+        const int g = r * 64 + lane;             // piece index within the tile
+        const int l = g / OC, c = g % OC;
+        const u32x4 v = t[l * OC + ((c + l) & (OC - 1))];
+        if ((size_t)g < pieces_left) st<NTS>(out + g, v);
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Plain 128-bit copy, the practical bandwidth ceiling the codec kernels are compared with.
 template <int U, bool NT>
