@@ -43,10 +43,13 @@ bool aligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 // Launch shapes, chosen by measurement on MI355X (HBM-bound kernels: more, smaller waves and
 // nontemporal loads stream best).
 constexpr int kQuantU = 2;          // units per lane, quantize
-constexpr bool kQuantNTL = true, kQuantNTS = false;
+constexpr bool kQuantNTL = true, kQuantNTS = true;
 constexpr int kReduceU = 4;         // units per lane, dequant-reduce
-constexpr int kReduceRC = 8;        // ranks loaded together
-constexpr bool kReduceNTL = true, kReduceNTS = true;
+constexpr int kReduceRC = 8;        // ranks loaded together, unit form
+constexpr bool kReduceNTL = true, kReduceNTS = false;
+// ranks loaded together, tile form: 4 for one 128-bit load per rank, 2 when a chunk's codes take
+// several narrower loads
+template <class E> constexpr int tile_rc() { return E::bits == 4 ? 4 : 2; }
 constexpr int kCopyU = 1;
 constexpr bool kHw = true;          // use the scaled-conversion instructions where exact
 
@@ -99,11 +102,11 @@ int launch_reduce(const ReduceArgs &a, bool out_bf16, hipStream_t st)
         const size_t chunks = a.units / 4;
         const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads));
         if (out_bf16)
-            hipLaunchKernelGGL((dequant_reduce_tile_kernel<E, B, true, kReduceRC, kReduceNTL,
+            hipLaunchKernelGGL((dequant_reduce_tile_kernel<E, B, true, tile_rc<E>(), kReduceNTL,
                                                            kReduceNTS, kHw>),
                                grid, dim3(kThreads), 0, st, a);
         else
-            hipLaunchKernelGGL((dequant_reduce_tile_kernel<E, B, false, kReduceRC, kReduceNTL,
+            hipLaunchKernelGGL((dequant_reduce_tile_kernel<E, B, false, tile_rc<E>(), kReduceNTL,
                                                            kReduceNTS, kHw>),
                                grid, dim3(kThreads), 0, st, a);
     } else {
