@@ -201,6 +201,64 @@ def requantize_chunk(fmt: Format, reduced: torch.Tensor, tp: int, chunk: int,
     return codes, scales
 
 
+class Launch:
+    """A library call with its arguments already marshalled: for loops that issue the same call
+    on the same buffers many times (serving loops, benchmarks).  Calling it enqueues the kernel
+    on ``stream`` (default: torch's current stream at call time).  It keeps the tensors alive."""
+
+    __slots__ = ("_fn", "_args", "_keep", "_what")
+
+    def __init__(self, fn, args, keep, what):
+        self._fn, self._args, self._keep, self._what = fn, args, keep, what
+
+    def __call__(self, stream=None) -> None:
+        s = stream.cuda_stream if stream is not None else torch.cuda.current_stream().cuda_stream
+        rc = self._fn(*self._args, s)
+        if rc != 0:
+            raise MxcError(rc, self._what)
+
+
+def prepare_quantize_batched(fmt: Format, xs: Sequence[torch.Tensor],
+                             codes: Sequence[torch.Tensor], scales: Sequence[torch.Tensor]) -> Launch:
+    for x in xs:
+        _dev(x, torch.bfloat16, "x")
+    for c, s_ in zip(codes, scales):
+        _dev(c, torch.uint8, "codes")
+        _dev(s_, torch.uint8, "scales")
+    tokens, hidden = xs[0].shape
+    f = fmt.c()
+    args = (ctypes.byref(f), len(xs), _ptrs(xs), tokens, hidden, _ptrs(codes), _ptrs(scales))
+    return Launch(lib().mxc_quantize_batched, args, (f, list(xs), list(codes), list(scales)),
+                  "mxc_quantize_batched")
+
+
+def prepare_dequant_reduce(fmt: Format, codes: Sequence[torch.Tensor],
+                           scales: Sequence[torch.Tensor], tokens: int, hidden: int,
+                           out: torch.Tensor) -> Launch:
+    for c, s_ in zip(codes, scales):
+        _dev(c, torch.uint8, "codes")
+        _dev(s_, torch.uint8, "scales")
+    _dev(out, out.dtype, "out")
+    dt = {torch.float32: MXC_F32, torch.bfloat16: MXC_BF16}[out.dtype]
+    f = fmt.c()
+    args = (ctypes.byref(f), len(codes), _ptrs(codes), _ptrs(scales), tokens, hidden,
+            out.data_ptr(), dt)
+    return Launch(lib().mxc_dequant_reduce, args, (f, list(codes), list(scales), out),
+                  "mxc_dequant_reduce")
+
+
+def prepare_requantize_chunk(fmt: Format, reduced: torch.Tensor, tp: int, chunk: int,
+                             codes: torch.Tensor, scales: torch.Tensor) -> Launch:
+    _dev(reduced, reduced.dtype, "reduced")
+    tokens, hidden = reduced.shape
+    dt = MXC_F32 if reduced.dtype == torch.float32 else MXC_BF16
+    f = fmt.c()
+    args = (ctypes.byref(f), reduced.data_ptr(), dt, tokens, hidden, tp, chunk,
+            codes.data_ptr(), scales.data_ptr())
+    return Launch(lib().mxc_requantize_chunk, args, (f, reduced, codes, scales),
+                  "mxc_requantize_chunk")
+
+
 def copy_probe(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
     nbytes = src.numel() * src.element_size()
     _check(lib().mxc_copy_probe(dst.data_ptr(), src.data_ptr(), nbytes, _stream(stream)),

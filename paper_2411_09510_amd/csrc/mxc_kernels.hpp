@@ -639,11 +639,11 @@ __global__ __launch_bounds__(kThreads) void dequant_reduce_tile_kernel(ReduceArg
 #pragma unroll
             for (int k = 0; k < W; ++k) cw[i][k] = 0u;
             if (on) {
+                typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
                 if (W == 4) {
                     const u32x4 v = ld<NTL>((const u32x4 *)cp);
                     cw[i][0] = v.x; cw[i][1] = v.y; cw[i][2] = v.z; cw[i][3 < W ? 3 : 0] = v.w;
                 } else if (W == 6) {
-                    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 #pragma unroll
                     for (int k = 0; k < 3; ++k) {
                         const u32x2 v = ld<NTL>((const u32x2 *)cp + k);
