@@ -117,6 +117,18 @@ int mxc_requantize_chunk(const mxc_format *fmt, const void *reduced, int in_dtyp
                          int64_t tokens, int64_t hidden, int tp, int chunk, void *codes_chunk,
                          void *scales_chunk, void *hip_stream);
 
+/* Fused form of the reduce-scatter leg (extension): exactly the result of
+ *   mxc_dequant_reduce(fmt, tp, codes, scales, tokens, hidden, tmp, MXC_F32) followed by
+ *   mxc_requantize_chunk(fmt, tmp, MXC_F32, tokens, hidden, 1, 0, codes_out, scales_out)
+ * bit for bit, without the binary32 tensor ever reaching memory.  Here [tokens x hidden] is the
+ * row chunk a rank owns and codes/scales are the tp compressed copies of that chunk it received
+ * (host arrays of tp device pointers); codes_out/scales_out receive the packed arrays of the
+ * re-quantized sum.  Requires tokens*hidden to be a multiple of 32 (always true for block 32),
+ * MXC_ERR_SHAPE otherwise. */
+int mxc_dequant_reduce_requantize(const mxc_format *fmt, int tp, const void *const *codes,
+                                  const void *const *scales, int64_t tokens, int64_t hidden,
+                                  void *codes_out, void *scales_out, void *hip_stream);
+
 /* Measurement aid: copy `bytes` (a multiple of 16, both pointers 16-byte aligned) from src to
  * dst on the device with 128-bit loads and stores.  Its rate is the practical ceiling the
  * codec kernels are compared with. */

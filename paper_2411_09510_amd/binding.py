@@ -78,6 +78,9 @@ def lib() -> ctypes.CDLL:
                                          vp, ci, vp]
         L.mxc_requantize_chunk.restype = ci
         L.mxc_requantize_chunk.argtypes = [fp, vp, ci, i64, i64, ci, ci, vp, vp, vp]
+        L.mxc_dequant_reduce_requantize.restype = ci
+        L.mxc_dequant_reduce_requantize.argtypes = [fp, ci, ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                                    i64, i64, vp, vp, vp]
         L.mxc_copy_probe.restype = ci
         L.mxc_copy_probe.argtypes = [vp, vp, ctypes.c_size_t, vp]
         _lib = L
@@ -201,6 +204,25 @@ def requantize_chunk(fmt: Format, reduced: torch.Tensor, tp: int, chunk: int,
     return codes, scales
 
 
+def dequant_reduce_requantize(fmt: Format, codes: Sequence[torch.Tensor],
+                              scales: Sequence[torch.Tensor], tokens: int, hidden: int,
+                              codes_out: Optional[torch.Tensor] = None,
+                              scales_out: Optional[torch.Tensor] = None, stream=None):
+    """Fused dequant-reduce + requantize of a row chunk: the tp compressed copies of a
+    [tokens, hidden] chunk in, the packed arrays of the re-quantized sum out."""
+    for c, s_ in zip(codes, scales):
+        _dev(c, torch.uint8, "codes")
+        _dev(s_, torch.uint8, "scales")
+    if codes_out is None or scales_out is None:
+        codes_out, scales_out = _alloc_packed(fmt, tokens, hidden, codes[0].device)
+    f = fmt.c()
+    _check(lib().mxc_dequant_reduce_requantize(ctypes.byref(f), len(codes), _ptrs(codes),
+                                               _ptrs(scales), tokens, hidden,
+                                               codes_out.data_ptr(), scales_out.data_ptr(),
+                                               _stream(stream)), "mxc_dequant_reduce_requantize")
+    return codes_out, scales_out
+
+
 class Launch:
     """A library call with its arguments already marshalled: for loops that issue the same call
     on the same buffers many times (serving loops, benchmarks).  Calling it enqueues the kernel
@@ -245,6 +267,20 @@ def prepare_dequant_reduce(fmt: Format, codes: Sequence[torch.Tensor],
             out.data_ptr(), dt)
     return Launch(lib().mxc_dequant_reduce, args, (f, list(codes), list(scales), out),
                   "mxc_dequant_reduce")
+
+
+def prepare_dequant_reduce_requantize(fmt: Format, codes: Sequence[torch.Tensor],
+                                      scales: Sequence[torch.Tensor], tokens: int, hidden: int,
+                                      codes_out: torch.Tensor, scales_out: torch.Tensor) -> Launch:
+    for c, s_ in zip(codes, scales):
+        _dev(c, torch.uint8, "codes")
+        _dev(s_, torch.uint8, "scales")
+    f = fmt.c()
+    args = (ctypes.byref(f), len(codes), _ptrs(codes), _ptrs(scales), tokens, hidden,
+            codes_out.data_ptr(), scales_out.data_ptr())
+    return Launch(lib().mxc_dequant_reduce_requantize, args,
+                  (f, list(codes), list(scales), codes_out, scales_out),
+                  "mxc_dequant_reduce_requantize")
 
 
 def prepare_requantize_chunk(fmt: Format, reduced: torch.Tensor, tp: int, chunk: int,

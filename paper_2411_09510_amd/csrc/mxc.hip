@@ -42,7 +42,8 @@ bool aligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
 // Launch shapes, chosen by measurement on MI355X (HBM-bound kernels: more, smaller waves and
 // nontemporal loads stream best).
-constexpr int kQuantU = 2;          // units per lane, quantize
+constexpr int kQuantU = 2;          // units per lane, quantize from bf16
+constexpr int kQuantU32 = 1;        // units per lane, quantize from binary32 (LDS-transposed loads)
 constexpr bool kQuantNTL = true, kQuantNTS = true;
 constexpr int kReduceU = 4;         // units per lane, dequant-reduce
 constexpr int kReduceRC = 8;        // ranks loaded together, unit form
@@ -62,8 +63,9 @@ unsigned grid_for(size_t units, int per_lane)
 template <class E, int B, bool SRC32>
 int launch_quantize(const QuantArgs &a, int n, hipStream_t st)
 {
-    hipLaunchKernelGGL((quantize_kernel<E, B, SRC32, kQuantU, kQuantNTL, kQuantNTS, kHw>),
-                       dim3(grid_for(a.units, kQuantU), (unsigned)n), dim3(kThreads), 0, st, a);
+    constexpr int U = SRC32 ? kQuantU32 : kQuantU;
+    hipLaunchKernelGGL((quantize_kernel<E, B, SRC32, U, kQuantNTL, kQuantNTS, kHw, SRC32>),
+                       dim3(grid_for(a.units, U), (unsigned)n), dim3(kThreads), 0, st, a);
     return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_HIP;
 }
 
@@ -124,6 +126,43 @@ int launch_reduce(const ReduceArgs &a, bool out_bf16, hipStream_t st)
     return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_HIP;
 }
 
+template <class E, int B>
+int launch_fused(const ReduceArgs &a, hipStream_t st)
+{
+    const size_t chunks = a.units / 4;
+    const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads));
+    hipLaunchKernelGGL((dequant_reduce_tile_kernel<E, B, false, tile_rc<E>(), kReduceNTL, kQuantNTS,
+                                                   kHw, true>),
+                       grid, dim3(kThreads), 0, st, a);
+    return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_HIP;
+}
+
+template <class E>
+int fused_by_block(int block, const ReduceArgs &a, hipStream_t st)
+{
+    switch (block) {
+    case 8: return launch_fused<E, 8>(a, st);
+    case 16: return launch_fused<E, 16>(a, st);
+    default: return launch_fused<E, 32>(a, st);
+    }
+}
+
+int fused_by_format(const mxc_format *f, const ReduceArgs &a, hipStream_t st)
+{
+    switch (f->ebits * 10 + f->mbits) {
+    case 11: return fused_by_block<Elem<1, 1>>(f->block, a, st);
+    case 12: return fused_by_block<Elem<1, 2>>(f->block, a, st);
+    case 13: return fused_by_block<Elem<1, 3>>(f->block, a, st);
+    case 14: return fused_by_block<Elem<1, 4>>(f->block, a, st);
+    case 21: return fused_by_block<Elem<2, 1>>(f->block, a, st);
+    case 22: return fused_by_block<Elem<2, 2>>(f->block, a, st);
+    case 23: return fused_by_block<Elem<2, 3>>(f->block, a, st);
+    case 31: return fused_by_block<Elem<3, 1>>(f->block, a, st);
+    case 32: return fused_by_block<Elem<3, 2>>(f->block, a, st);
+    default: return MXC_ERR_FORMAT;
+    }
+}
+
 template <class E>
 int reduce_by_block(int block, const ReduceArgs &a, bool out_bf16, hipStream_t st)
 {
@@ -176,6 +215,31 @@ int quantize_common(const mxc_format *fmt, int n, const void *const *x, bool src
     hipStream_t st = (hipStream_t)hip_stream;
     return src32 ? quantize_by_format<true>(fmt, a, n, st)
                  : quantize_by_format<false>(fmt, a, n, st);
+}
+
+// Validation shared by the reduce entry points; fills the pointer tables of `a`.
+int reduce_args(const mxc_format *fmt, int tp, const void *const *codes, const void *const *scales,
+                int64_t tokens, int64_t hidden, ReduceArgs *a)
+{
+    if (!fmt || !codes || !scales) return MXC_ERR_NULL;
+    if (!format_ok(fmt)) return MXC_ERR_FORMAT;
+    if (tp < 1 || tp > MXC_MAX_TP) return MXC_ERR_TP;
+    int rc = shape_units(fmt, tokens, hidden, &a->units);
+    if (rc != MXC_OK) return rc;
+    for (int r = 0; r < tp; ++r) {
+        if (!codes[r] || !scales[r]) return MXC_ERR_NULL;
+        if (!aligned(codes[r], 16) || !aligned(scales[r], 4)) return MXC_ERR_ALIGN;
+    }
+    for (int r = 0; r < 32; ++r) {
+        a->codes[r] = codes[r < tp ? r : 0];
+        a->scales[r] = scales[r < tp ? r : 0];
+    }
+    a->out = nullptr;
+    a->codes_out = nullptr;
+    a->scales_out = nullptr;
+    a->tp = tp;
+    a->sf = scale_fmt(fmt);
+    return MXC_OK;
 }
 
 }  // namespace
@@ -239,27 +303,32 @@ int mxc_dequant_reduce(const mxc_format *fmt, int tp, const void *const *codes,
                        const void *const *scales, int64_t tokens, int64_t hidden, void *out,
                        int out_dtype, void *hip_stream)
 {
-    if (!fmt || !codes || !scales || !out) return MXC_ERR_NULL;
-    if (!format_ok(fmt)) return MXC_ERR_FORMAT;
-    if (tp < 1 || tp > MXC_MAX_TP) return MXC_ERR_TP;
-    if (out_dtype != MXC_F32 && out_dtype != MXC_BF16) return MXC_ERR_DTYPE;
+    if (!out) return MXC_ERR_NULL;
+    if (out_dtype != MXC_F32 && out_dtype != MXC_BF16)
+        return (!fmt || !codes || !scales) ? MXC_ERR_NULL : MXC_ERR_DTYPE;
     ReduceArgs a;
-    int rc = shape_units(fmt, tokens, hidden, &a.units);
+    int rc = reduce_args(fmt, tp, codes, scales, tokens, hidden, &a);
     if (rc != MXC_OK) return rc;
-    for (int r = 0; r < tp; ++r) {
-        if (!codes[r] || !scales[r]) return MXC_ERR_NULL;
-        if (!aligned(codes[r], 16) || !aligned(scales[r], 4)) return MXC_ERR_ALIGN;
-    }
     if (!aligned(out, 16)) return MXC_ERR_ALIGN;
     if (a.units == 0) return MXC_OK;
-    for (int r = 0; r < 32; ++r) {
-        a.codes[r] = codes[r < tp ? r : 0];
-        a.scales[r] = scales[r < tp ? r : 0];
-    }
     a.out = out;
-    a.tp = tp;
-    a.sf = scale_fmt(fmt);
     return reduce_by_format(fmt, a, out_dtype == MXC_BF16, (hipStream_t)hip_stream);
+}
+
+int mxc_dequant_reduce_requantize(const mxc_format *fmt, int tp, const void *const *codes,
+                                  const void *const *scales, int64_t tokens, int64_t hidden,
+                                  void *codes_out, void *scales_out, void *hip_stream)
+{
+    if (!codes_out || !scales_out) return MXC_ERR_NULL;
+    ReduceArgs a;
+    int rc = reduce_args(fmt, tp, codes, scales, tokens, hidden, &a);
+    if (rc != MXC_OK) return rc;
+    if (a.units % 4) return MXC_ERR_SHAPE;
+    if (!aligned(codes_out, 16) || !aligned(scales_out, 4)) return MXC_ERR_ALIGN;
+    if (a.units == 0) return MXC_OK;
+    a.codes_out = codes_out;
+    a.scales_out = scales_out;
+    return fused_by_format(fmt, a, (hipStream_t)hip_stream);
 }
 
 int mxc_requantize_chunk(const mxc_format *fmt, const void *reduced, int in_dtype, int64_t tokens,

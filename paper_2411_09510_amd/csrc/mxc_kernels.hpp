@@ -348,15 +348,50 @@ __device__ __forceinline__ uint64_t encode_unit_hw(const u32x4 (&w)[SRC32 ? 2 : 
     }
 }
 
+// Shared exponent of a block from the biased exponent field of its maximum, and the unit's eight
+// packed codes.  Returns the scale byte in *scale_byte.
+template <class E, bool SRC32, bool HW>
+__device__ __forceinline__ uint64_t encode_unit(const u32x4 (&w)[SRC32 ? 2 : 1], int expfield,
+                                                const ScaleFmt &sf, int *scale_byte)
+{
+    constexpr bool kHw = HW && E::hw != HW_NONE;
+    // shared exponent: floor(log2 max) - emax, as a scale code, clamped to the scale format
+    const int unclamped = expfield - 127 - E::emax + sf.sbias;
+    const bool finite = expfield != 255;
+    const int sc = finite ? min(max(unclamped, 0), sf.smax) : sf.nonfinite;
+    const int e = sc - sf.sbias;
+    *scale_byte = sc;
+
+    uint64_t packed;
+    if (kHw) {
+        // divide by 2^(e - beta + hw_bias): the element format's smallest normal then falls on
+        // the hardware format's smallest normal.  Usable while that power of two has a binary32
+        // exponent field and (for the 8-bit formats) the scale's upper clamp is idle, which is
+        // what bounds |p| below 2^(emax+1).
+        const int field = e - E::beta + E::hw_bias + 127;
+        const bool ok = field >= 0 && field <= 254 && (E::hw == HW_FP4 || unclamped <= sf.smax);
+        if (__builtin_amdgcn_ballot_w64(!ok && finite) == 0) {
+            packed = encode_unit_hw<E, SRC32>(w, __uint_as_float((uint32_t)max(field, 0) << 23));
+        } else {
+            packed = encode_unit_generic<E, SRC32>(w, -e);
+        }
+    } else {
+        packed = encode_unit_generic<E, SRC32>(w, -e);
+    }
+    return finite ? packed : 0;
+}
+
 // SRC32 = false: bfloat16 input, one 128-bit load per unit.
 // SRC32 = true : binary32 input, two 128-bit loads per unit.
 // U: units per lane.  NTL/NTS: nontemporal loads / stores.  HW: use scaled conversions.
-template <class E, int B, bool SRC32, int U, bool NTL, bool NTS, bool HW>
+// XPOSE (binary32 input only): load the wave's 32-byte units as contiguous 16-byte pieces and
+// hand each lane its unit through a wave-private LDS tile, instead of two 16-byte loads per lane
+// that each use half of every cache line they touch.
+template <class E, int B, bool SRC32, int U, bool NTL, bool NTS, bool HW, bool XPOSE = false>
 __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantArgs a)
 {
     constexpr int G = B / 8;                     // lanes per block
     constexpr int NW = SRC32 ? 2 : 1;
-    constexpr bool kHw = HW && E::hw != HW_NONE;
     const int lane = (int)(threadIdx.x & 63);
     const int wave = (int)(threadIdx.x >> 6);
     const size_t wave_base =
@@ -368,6 +403,30 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantArgs a)
 
     u32x4 w[U][NW];
     bool valid[U];
+    if (XPOSE && SRC32) {
+        __shared__ u32x4 xtile[kThreads / 64][XPOSE ? U * 64 * 2 : 1];
+        u32x4 *t = xtile[wave];
+        const u32x4 *src = (const u32x4 *)xin + wave_base * 2;       // 2 pieces per unit
+        const size_t pieces_left = wave_base < a.units ? (a.units - wave_base) * 2 : 0;
+        u32x4 pv[U * 2];
+#pragma unroll
+        for (int k = 0; k < U * 2; ++k) {
+            const int piece = k * 64 + lane;
+            pv[k] = (size_t)piece < pieces_left ? ld<NTL>(src + piece) : u32x4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int k = 0; k < U * 2; ++k) t[k * 64 + lane] = pv[k];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t unit = wave_base + (size_t)(u * 64 + lane);
+            valid[u] = unit < a.units;
+            w[u][0] = t[(u * 64 + lane) * 2];
+            w[u][NW - 1] = t[(u * 64 + lane) * 2 + 1];
+        }
+    } else {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const size_t unit = wave_base + (size_t)(u * 64 + lane);
@@ -376,6 +435,7 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantArgs a)
 #pragma unroll
         for (int h = 0; h < NW; ++h)
             w[u][h] = valid[u] ? ld<NTL>((const u32x4 *)xin + unit * NW + h) : zero;
+    }
     }
 
     int my_scale = 0;                            // the scale byte this lane will store
@@ -397,29 +457,8 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantArgs a)
             m = max(m & 0xFFFFu, m >> 16);
             expfield = (int)(block_max<B>(m) >> 7);
         }
-        // shared exponent: floor(log2 max) - emax, as a scale code, clamped to the scale format
-        const int unclamped = expfield - 127 - E::emax + sf.sbias;
-        const bool finite = expfield != 255;
-        const int sc = finite ? min(max(unclamped, 0), sf.smax) : sf.nonfinite;
-        const int e = sc - sf.sbias;
-
-        uint64_t packed;
-        if (kHw) {
-            // divide by 2^(e - beta + hw_bias): the element format's smallest normal then falls
-            // on the hardware format's smallest normal.  Usable while that power of two has a
-            // binary32 exponent field and (for the 8-bit formats) the scale's upper clamp is
-            // idle, which is what bounds |p| below 2^(emax+1).
-            const int field = e - E::beta + E::hw_bias + 127;
-            const bool ok = field >= 0 && field <= 254 && (E::hw == HW_FP4 || unclamped <= sf.smax);
-            if (__builtin_amdgcn_ballot_w64(!ok && finite) == 0) {
-                packed = encode_unit_hw<E, SRC32>(w[u], __uint_as_float((uint32_t)max(field, 0) << 23));
-            } else {
-                packed = encode_unit_generic<E, SRC32>(w[u], -e);
-            }
-        } else {
-            packed = encode_unit_generic<E, SRC32>(w[u], -e);
-        }
-        if (!finite) packed = 0;
+        int sc;
+        const uint64_t packed = encode_unit<E, SRC32, HW>(w[u], expfield, sf, &sc);
         store_codes<E::bits, NTS>(codes, unit, packed, valid[u]);
 
         // Every lane of a block knows the block's scale.
@@ -444,7 +483,9 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantArgs a)
 struct ReduceArgs {
     const void *codes[32];
     const void *scales[32];
-    void *out;
+    void *out;          // reduced tensor, or NULL for the fused form
+    void *codes_out;    // fused form: packed codes of the re-quantized sum
+    void *scales_out;   // fused form: its scale bytes
     size_t units;
     int tp;
     ScaleFmt sf;
@@ -604,14 +645,17 @@ __device__ __forceinline__ uint32_t stream_bits_rt(const uint32_t (&s)[NW], int 
 // as the format allows.  The lane's 32 sums are then exchanged through a wave-private LDS tile so
 // that the wave writes its 8 KiB (4 KiB for bf16) of output as contiguous 128-bit stores.
 
-template <class E, int B, bool OUT_BF16, int RC, bool NTL, bool NTS, bool HW>
+// FUSED: instead of storing the sums, quantize them again in the lane that holds them (same
+// rule as the quantizer applied to binary32 input) and store codes and scales; bit-identical to
+// running the unfused kernels one after the other.
+template <class E, int B, bool OUT_BF16, int RC, bool NTL, bool NTS, bool HW, bool FUSED = false>
 __global__ __launch_bounds__(kThreads) void dequant_reduce_tile_kernel(ReduceArgs a)
 {
     constexpr int NB = 32 / B;                   // blocks (scales) per chunk
     constexpr int W = E::bits;                   // dwords of codes per chunk
     constexpr bool kHw = HW && E::hw != HW_NONE;
     constexpr int OC = OUT_BF16 ? 4 : 8;         // 16-byte output pieces per lane
-    __shared__ u32x4 tile[kThreads / 64][64 * OC];
+    __shared__ u32x4 tile[kThreads / 64][FUSED ? 1 : 64 * OC];
 
     const int lane = (int)(threadIdx.x & 63);
     const int wave = (int)(threadIdx.x >> 6);
@@ -714,6 +758,62 @@ __global__ __launch_bounds__(kThreads) void dequant_reduce_tile_kernel(ReduceArg
 #pragma unroll
             for (int j = 0; j < B; ++j) acc[n * B + j] = __uint_as_float(0x7FC00000u);
         }
+
+    if (FUSED) {
+        // The lane holds whole blocks: block maximum, scale and codes need no other lane.
+        uint32_t cw[W];
+#pragma unroll
+        for (int k = 0; k < W; ++k) cw[k] = 0u;
+        uint32_t sbytes = 0;
+#pragma unroll
+        for (int n = 0; n < NB; ++n) {
+            uint32_t m = 0;
+#pragma unroll
+            for (int j = 0; j < B; ++j) m = max(m, __float_as_uint(acc[n * B + j]) & 0x7FFFFFFFu);
+            const int expfield = (int)(m >> 23);
+            int sc = 0;
+#pragma unroll
+            for (int g = 0; g < B / 8; ++g) {
+                const int first = n * B + g * 8;
+                u32x4 w2[2];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    w2[0][j] = __float_as_uint(acc[first + j]);
+                    w2[1][j] = __float_as_uint(acc[first + 4 + j]);
+                }
+                const uint64_t packed = encode_unit<E, true, HW>(w2, expfield, sf, &sc);
+                // 8b bits at bit first*b of the chunk's stream (constant positions)
+                const int pos = first * W;
+                cw[pos >> 5] |= (uint32_t)(packed << (pos & 31));
+                if ((pos & 31) + 8 * W > 32) {
+                    const uint64_t rest = packed >> (32 - (pos & 31));
+                    cw[((pos >> 5) + 1) < W ? (pos >> 5) + 1 : 0] |= (uint32_t)rest;
+                    if ((pos & 31) + 8 * W > 64)
+                        cw[((pos >> 5) + 2) < W ? (pos >> 5) + 2 : 0] |= (uint32_t)(rest >> 32);
+                }
+            }
+            sbytes |= (uint32_t)sc << (8 * n);
+        }
+        if (valid) {
+            uint32_t *cp = (uint32_t *)a.codes_out + chunk * W;
+            if (W == 4) {
+                st<NTS>((u32x4 *)cp, u32x4{cw[0], cw[1], cw[2], cw[3 < W ? 3 : 0]});
+            } else if (W == 6) {
+                typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+                for (int k = 0; k < 3; ++k)
+                    st<NTS>((u32x2 *)cp + k, u32x2{cw[(2 * k) < W ? 2 * k : 0], cw[(2 * k + 1) < W ? 2 * k + 1 : 0]});
+            } else {
+#pragma unroll
+                for (int k = 0; k < W; ++k) st<NTS>(cp + k, cw[k]);
+            }
+            uint8_t *sp = (uint8_t *)a.scales_out + chunk * NB;
+            if (NB == 1) *sp = (uint8_t)sbytes;
+            else if (NB == 2) *(uint16_t *)sp = (uint16_t)sbytes;
+            else *(uint32_t *)sp = sbytes;
+        }
+        return;
+    }
 
     // Exchange through LDS.  Lane l owns output pieces l*OC .. l*OC+OC-1 of the wave's tile; piece
     // c is written to slot (c + l) % OC of the lane's row so that both the row-wise writes and

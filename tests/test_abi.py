@@ -24,7 +24,7 @@ def declared_functions():
 def test_header_functions_are_exported(L):
     names = declared_functions()
     assert {"mxc_quantize", "mxc_quantize_batched", "mxc_dequant_reduce", "mxc_requantize_chunk",
-            "mxc_packed_sizes", "mxc_strerror", "mxc_copy_probe"} <= set(names)
+            "mxc_dequant_reduce_requantize", "mxc_packed_sizes", "mxc_strerror", "mxc_copy_probe"} <= set(names)
     for n in names:
         assert getattr(L, n) is not None, n
 
@@ -83,6 +83,11 @@ def test_host_side_argument_errors(L):
     assert L.mxc_requantize_chunk(fp, good, 0, 8, 64, 4, 4, good, good, None) == -5
     assert L.mxc_requantize_chunk(fp, good, 0, 8, 64, 4, -1, good, good, None) == -5
     assert L.mxc_requantize_chunk(fp, good, 5, 8, 64, 4, 0, good, good, None) == -7
+    assert L.mxc_dequant_reduce_requantize(fp, 2, arr, arr, 4, 64, good, None, None) == -1
+    assert L.mxc_dequant_reduce_requantize(fp, 2, arr, arr, 4, 64, good, 0x10002, None) == -4
+    assert L.mxc_dequant_reduce_requantize(fp, 40, arr, arr, 4, 64, good, good, None) == -5
+    small = _CFormat(2, 1, 8, 8)
+    assert L.mxc_dequant_reduce_requantize(ctypes.byref(small), 2, arr, arr, 1, 8, good, good, None) == -3
     assert L.mxc_copy_probe(good, good, 24, None) == -3
     assert L.mxc_copy_probe(good, odd, 32, None) == -4
     assert L.mxc_copy_probe(good, good, 0, None) == 0

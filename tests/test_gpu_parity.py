@@ -286,6 +286,35 @@ def test_requantize_chunks(mxc, oracle_mod, x, y, B):
         assert np.array_equal(host(c16), oracle_mod.pack(fo, oc))
 
 
+@pytest.mark.parametrize("x,y,B", [(2, 1, 32), (2, 1, 16), (2, 1, 8), (2, 2, 32), (3, 2, 32), (3, 2, 16),
+                                   (1, 1, 32), (1, 3, 8), (2, 3, 32), (3, 1, 16), (1, 4, 32)])
+def test_fused_reduce_requantize_equals_unfused_pair(mxc, oracle_mod, x, y, B):
+    """The fused call must give, bit for bit, what dequant_reduce to binary32 followed by
+    requantize gives, and both must match the oracle's pipeline."""
+    rng = np.random.default_rng(x * 100 + y * 10 + B)
+    for tp, T, H in ((8, 16, 1024), (3, 5, 2080), (1, 2, 64)):
+        w = workloads.Workload("fused", tp, T, H, seed=60 + tp, n_outlier=2, outlier_mult=(20.0, 100.0))
+        fo, fg = oracle_mod.Format(x, y, B, 8), mxc.Format(x, y, B, 8)
+        ocs, oss = oracle_partials(oracle_mod, fo, w)
+        if tp == 3:                                   # arbitrary bytes too: NaN markers, far binades
+            ocs = [rng.integers(0, 2 ** fo.bits, size=(T, H), dtype=np.uint8) for _ in range(tp)]
+            oss = [rng.integers(90, 170, size=(T, H // B), dtype=np.uint8) for _ in range(tp)]
+            oss[1][0, ::4] = 255
+            oss[2][1, ::3] = 254
+            oss[0][2, ::5] = 0
+        packed = [torch.from_numpy(oracle_mod.pack(fo, c)).cuda() for c in ocs]
+        scales = [torch.from_numpy(s).cuda() for s in oss]
+        red = mxc.dequant_reduce(fg, packed, scales, T, H)
+        c2, s2 = mxc.requantize_chunk(fg, red, 1, 0)
+        cf, sf_ = mxc.dequant_reduce_requantize(fg, packed, scales, T, H)
+        torch.cuda.synchronize()
+        assert torch.equal(sf_, s2) and torch.equal(cf, c2)
+        want = oracle_mod.dequant_reduce(fo, ocs, oss)
+        oc, os_ = oracle_mod.quantize_f32(fo, want)
+        assert np.array_equal(host(sf_), os_)
+        assert np.array_equal(host(cf), oracle_mod.pack(fo, oc))
+
+
 def test_requantize_f32_rounding_corners(mxc, oracle_mod):
     """binary32 inputs a hair around rounding midpoints, which need all 24 significand bits."""
     rng = np.random.default_rng(21)
