@@ -110,6 +110,16 @@ int mxc_dequant_reduce(const mxc_format *fmt, int tp, const void *const *codes,
                        const void *const *scales, int64_t tokens, int64_t hidden, void *out,
                        int out_dtype, void *hip_stream);
 
+/* The reduction as the paper's Profiling section words it: a worker decompresses the partials
+ * of the N-1 other workers and adds its own partial uncompressed.  Like mxc_dequant_reduce, but
+ * the term of rank own_rank (0..tp-1) is read from own_x_bf16 (device, bf16 [tokens x hidden],
+ * exact in binary32) instead of being decoded; codes[own_rank] / scales[own_rank] are not read
+ * and may be NULL.  The order of the adds is still rank order, so the result differs between
+ * ranks only through which term is exact. */
+int mxc_dequant_reduce_own(const mxc_format *fmt, int tp, int own_rank, const void *own_x_bf16,
+                           const void *const *codes, const void *const *scales, int64_t tokens,
+                           int64_t hidden, void *out, int out_dtype, void *hip_stream);
+
 /* Quantize rows [chunk*tokens/tp, (chunk+1)*tokens/tp) of the reduced tensor (extension, see
  * top).  `reduced` is the whole [tokens x hidden] tensor of in_dtype (MXC_F32 or MXC_BF16);
  * codes_chunk / scales_chunk receive the packed arrays of a [tokens/tp x hidden] tensor. */

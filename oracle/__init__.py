@@ -173,6 +173,24 @@ def dequant_reduce(fmt: Format, codes_list, scales_list) -> np.ndarray:
     return out
 
 
+def dequant_reduce_own(fmt: Format, own_rank: int, own_bits: np.ndarray, codes_list,
+                       scales_list) -> np.ndarray:
+    """The same fold with rank ``own_rank`` contributing its raw bf16 partial (Profiling)."""
+    tp = len(codes_list)
+    own_bits = np.ascontiguousarray(own_bits, dtype=np.uint16)
+    T, H = own_bits.shape
+    cs = [None if c is None else np.ascontiguousarray(c, dtype=np.uint8) for c in codes_list]
+    ss = [None if s is None else np.ascontiguousarray(s, dtype=np.uint8) for s in scales_list]
+    out = np.empty((T, H), dtype=np.float32)
+    cp = (ctypes.c_void_p * tp)(*[None if c is None else c.ctypes.data for c in cs])
+    sp = (ctypes.c_void_p * tp)(*[None if s is None else s.ctypes.data for s in ss])
+    f = fmt.c()
+    _check(lib().mxo_dequant_reduce_own(ctypes.byref(f), ctypes.c_int(tp), ctypes.c_int(own_rank),
+                                        _ptr(own_bits), cp, sp, ctypes.c_int64(T),
+                                        ctypes.c_int64(H), _ptr(out)), "dequant_reduce_own")
+    return out
+
+
 def round_to_bf16(x: np.ndarray) -> np.ndarray:
     x = np.ascontiguousarray(x, dtype=np.float32)
     out = np.empty(x.shape, dtype=np.uint16)

@@ -346,6 +346,39 @@ int mxo_dequant_reduce(const mxo_format *f, int tp, const uint8_t *const *codes_
     return MXO_OK;
 }
 
+/* The reduction as the Profiling section words it: a worker decompresses the partials of the
+ * N-1 other workers and adds its own partial as it is.  Same left fold in rank order, but the
+ * term of rank own_rank is the bfloat16 value own_x[t,h] (exact in binary32);
+ * codes_unpacked[own_rank] and scales[own_rank] are not read. */
+int mxo_dequant_reduce_own(const mxo_format *f, int tp, int own_rank, const uint16_t *own_x,
+                           const uint8_t *const *codes_unpacked, const uint8_t *const *scales,
+                           int64_t tokens, int64_t hidden, float *out)
+{
+    if (!fmt_ok(f)) return MXO_ERR_FORMAT;
+    if (tp < 1 || tp > 32 || own_rank < 0 || own_rank >= tp) return MXO_ERR_TP;
+    if (tokens < 0 || hidden < 0 || hidden % f->block) return MXO_ERR_SHAPE;
+    int B = f->block;
+    int64_t nb = hidden / B;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < tokens; ++t)
+        for (int64_t h = 0; h < hidden; ++h) {
+            volatile float acc = 0.0f;
+            for (int r = 0; r < tp; ++r) {
+                float d;
+                if (r == own_rank) {
+                    d = (float)bf16_value(own_x[t * hidden + h]);
+                } else {
+                    double s = mxo_scale_value(f, scales[r][t * nb + h / B]);
+                    d = (float)(mxo_code_value(f, codes_unpacked[r][t * hidden + h]) * s);
+                }
+                if (r == 0) acc = d;
+                else { float a = acc; acc = a + d; }
+            }
+            out[t * hidden + h] = acc;
+        }
+    return MXO_OK;
+}
+
 /* binary32 -> bfloat16 bit pattern, round to nearest even; NaN -> 0x7FC0. */
 static uint16_t bf16_from_float(float v)
 {

@@ -78,6 +78,9 @@ def lib() -> ctypes.CDLL:
                                          vp, ci, vp]
         L.mxc_requantize_chunk.restype = ci
         L.mxc_requantize_chunk.argtypes = [fp, vp, ci, i64, i64, ci, ci, vp, vp, vp]
+        L.mxc_dequant_reduce_own.restype = ci
+        L.mxc_dequant_reduce_own.argtypes = [fp, ci, ci, vp, ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                             i64, i64, vp, ci, vp]
         L.mxc_dequant_reduce_requantize.restype = ci
         L.mxc_dequant_reduce_requantize.argtypes = [fp, ci, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                                     i64, i64, vp, vp, vp]
@@ -202,6 +205,30 @@ def requantize_chunk(fmt: Format, reduced: torch.Tensor, tp: int, chunk: int,
                                       chunk, codes.data_ptr(), scales.data_ptr(),
                                       _stream(stream)), "mxc_requantize_chunk")
     return codes, scales
+
+
+def dequant_reduce_own(fmt: Format, own_rank: int, own_x: torch.Tensor,
+                       codes: Sequence[Optional[torch.Tensor]],
+                       scales: Sequence[Optional[torch.Tensor]], out: Optional[torch.Tensor] = None,
+                       out_dtype=torch.float32, stream=None) -> torch.Tensor:
+    """Reduction with rank ``own_rank`` contributing its uncompressed bf16 partial ``own_x``;
+    ``codes[own_rank]`` / ``scales[own_rank]`` may be None."""
+    _dev(own_x, torch.bfloat16, "own_x")
+    tokens, hidden = own_x.shape
+    for r, (c, s_) in enumerate(zip(codes, scales)):
+        if r != own_rank:
+            _dev(c, torch.uint8, "codes")
+            _dev(s_, torch.uint8, "scales")
+    if out is None:
+        out = torch.empty((tokens, hidden), dtype=out_dtype, device=own_x.device)
+    dt = {torch.float32: MXC_F32, torch.bfloat16: MXC_BF16}[out.dtype]
+    cp = (ctypes.c_void_p * len(codes))(*[None if c is None else c.data_ptr() for c in codes])
+    sp = (ctypes.c_void_p * len(codes))(*[None if s_ is None else s_.data_ptr() for s_ in scales])
+    f = fmt.c()
+    _check(lib().mxc_dequant_reduce_own(ctypes.byref(f), len(codes), own_rank, own_x.data_ptr(),
+                                        cp, sp, tokens, hidden, out.data_ptr(), dt,
+                                        _stream(stream)), "mxc_dequant_reduce_own")
+    return out
 
 
 def dequant_reduce_requantize(fmt: Format, codes: Sequence[torch.Tensor],

@@ -96,34 +96,34 @@ int quantize_by_format(const mxc_format *f, const QuantArgs &a, int n, hipStream
     }
 }
 
-template <class E, int B>
-int launch_reduce(const ReduceArgs &a, bool out_bf16, hipStream_t st)
+template <class E, int B, bool OUT_BF16, bool OWN>
+int launch_reduce_as(const ReduceArgs &a, hipStream_t st)
 {
     if (a.units % 4 == 0) {
         // whole 32-element chunks: one lane per chunk, output staged through LDS
         const size_t chunks = a.units / 4;
         const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads));
-        if (out_bf16)
-            hipLaunchKernelGGL((dequant_reduce_tile_kernel<E, B, true, tile_rc<E>(), kReduceNTL,
-                                                           kReduceNTS, kHw>),
-                               grid, dim3(kThreads), 0, st, a);
-        else
-            hipLaunchKernelGGL((dequant_reduce_tile_kernel<E, B, false, tile_rc<E>(), kReduceNTL,
-                                                           kReduceNTS, kHw>),
-                               grid, dim3(kThreads), 0, st, a);
+        hipLaunchKernelGGL((dequant_reduce_tile_kernel<E, B, OUT_BF16, tile_rc<E>(), kReduceNTL,
+                                                       kReduceNTS, kHw, false, OWN>),
+                           grid, dim3(kThreads), 0, st, a);
     } else {
         // sizes that are not a multiple of 32 elements (only possible with blocks of 8 or 16)
         const dim3 grid(grid_for(a.units, kReduceU));
-        if (out_bf16)
-            hipLaunchKernelGGL((dequant_reduce_kernel<E, B, true, kReduceU, kReduceRC, kReduceNTL,
-                                                      kReduceNTS, kHw>),
-                               grid, dim3(kThreads), 0, st, a);
-        else
-            hipLaunchKernelGGL((dequant_reduce_kernel<E, B, false, kReduceU, kReduceRC, kReduceNTL,
-                                                      kReduceNTS, kHw>),
-                               grid, dim3(kThreads), 0, st, a);
+        hipLaunchKernelGGL((dequant_reduce_kernel<E, B, OUT_BF16, kReduceU, kReduceRC, kReduceNTL,
+                                                  kReduceNTS, kHw, OWN>),
+                           grid, dim3(kThreads), 0, st, a);
     }
     return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_HIP;
+}
+
+template <class E, int B>
+int launch_reduce(const ReduceArgs &a, bool out_bf16, hipStream_t st)
+{
+    const bool own = a.own_rank >= 0;
+    if (out_bf16) return own ? launch_reduce_as<E, B, true, true>(a, st)
+                             : launch_reduce_as<E, B, true, false>(a, st);
+    return own ? launch_reduce_as<E, B, false, true>(a, st)
+               : launch_reduce_as<E, B, false, false>(a, st);
 }
 
 template <class E, int B>
@@ -219,7 +219,8 @@ int quantize_common(const mxc_format *fmt, int n, const void *const *x, bool src
 
 // Validation shared by the reduce entry points; fills the pointer tables of `a`.
 int reduce_args(const mxc_format *fmt, int tp, const void *const *codes, const void *const *scales,
-                int64_t tokens, int64_t hidden, ReduceArgs *a)
+                int64_t tokens, int64_t hidden, ReduceArgs *a, int own_rank = -1,
+                const void *own_x = nullptr)
 {
     if (!fmt || !codes || !scales) return MXC_ERR_NULL;
     if (!format_ok(fmt)) return MXC_ERR_FORMAT;
@@ -227,6 +228,7 @@ int reduce_args(const mxc_format *fmt, int tp, const void *const *codes, const v
     int rc = shape_units(fmt, tokens, hidden, &a->units);
     if (rc != MXC_OK) return rc;
     for (int r = 0; r < tp; ++r) {
+        if (r == own_rank) continue;              // that rank's compressed arrays are not read
         if (!codes[r] || !scales[r]) return MXC_ERR_NULL;
         if (!aligned(codes[r], 16) || !aligned(scales[r], 4)) return MXC_ERR_ALIGN;
     }
@@ -234,6 +236,8 @@ int reduce_args(const mxc_format *fmt, int tp, const void *const *codes, const v
         a->codes[r] = codes[r < tp ? r : 0];
         a->scales[r] = scales[r < tp ? r : 0];
     }
+    a->own_rank = own_rank;
+    a->own_x = own_x;
     a->out = nullptr;
     a->codes_out = nullptr;
     a->scales_out = nullptr;
@@ -310,6 +314,23 @@ int mxc_dequant_reduce(const mxc_format *fmt, int tp, const void *const *codes,
     int rc = reduce_args(fmt, tp, codes, scales, tokens, hidden, &a);
     if (rc != MXC_OK) return rc;
     if (!aligned(out, 16)) return MXC_ERR_ALIGN;
+    if (a.units == 0) return MXC_OK;
+    a.out = out;
+    return reduce_by_format(fmt, a, out_dtype == MXC_BF16, (hipStream_t)hip_stream);
+}
+
+int mxc_dequant_reduce_own(const mxc_format *fmt, int tp, int own_rank, const void *own_x_bf16,
+                           const void *const *codes, const void *const *scales, int64_t tokens,
+                           int64_t hidden, void *out, int out_dtype, void *hip_stream)
+{
+    if (!out || !own_x_bf16) return MXC_ERR_NULL;
+    if (out_dtype != MXC_F32 && out_dtype != MXC_BF16)
+        return (!fmt || !codes || !scales) ? MXC_ERR_NULL : MXC_ERR_DTYPE;
+    if (tp >= 1 && tp <= MXC_MAX_TP && (own_rank < 0 || own_rank >= tp)) return MXC_ERR_TP;
+    ReduceArgs a;
+    int rc = reduce_args(fmt, tp, codes, scales, tokens, hidden, &a, own_rank, own_x_bf16);
+    if (rc != MXC_OK) return rc;
+    if (!aligned(out, 16) || !aligned(own_x_bf16, 16)) return MXC_ERR_ALIGN;
     if (a.units == 0) return MXC_OK;
     a.out = out;
     return reduce_by_format(fmt, a, out_dtype == MXC_BF16, (hipStream_t)hip_stream);

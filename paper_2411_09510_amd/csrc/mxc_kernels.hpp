@@ -486,10 +486,23 @@ struct ReduceArgs {
     void *out;          // reduced tensor, or NULL for the fused form
     void *codes_out;    // fused form: packed codes of the re-quantized sum
     void *scales_out;   // fused form: its scale bytes
+    const void *own_x;  // OWN form: this rank's uncompressed bf16 partial
+    int own_rank;       // OWN form: the rank whose term is read from own_x, else -1
     size_t units;
     int tp;
     ScaleFmt sf;
 };
+
+// Adds (or, for the first rank, assigns) eight bfloat16 values, given as four dwords, to acc.
+__device__ __forceinline__ void add_raw_bf16(const u32x4 v, bool first, float *acc)
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float lo = __uint_as_float(v[j] << 16), hi = __uint_as_float(v[j] & 0xFFFF0000u);
+        acc[2 * j] = first ? lo : acc[2 * j] + lo;
+        acc[2 * j + 1] = first ? hi : acc[2 * j + 1] + hi;
+    }
+}
 
 // Integer-path decode of code j of `v` to binary32 times 2^k (exact): the magnitude code,
 // shifted so that its mantissa sits at the top of binary32's fraction field, is
@@ -555,7 +568,9 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f)
 }
 
 // RC: ranks whose loads are issued together.
-template <class E, int B, bool OUT_BF16, int U, int RC, bool NTL, bool NTS, bool HW>
+// OWN: rank a.own_rank contributes its uncompressed bf16 partial instead of a decoded one (the
+// paper's Profiling setup: a worker decompresses the N-1 partials of the other workers).
+template <class E, int B, bool OUT_BF16, int U, int RC, bool NTL, bool NTS, bool HW, bool OWN = false>
 __global__ __launch_bounds__(kThreads) void dequant_reduce_kernel(ReduceArgs a)
 {
     constexpr int G = B / 8;
@@ -577,14 +592,18 @@ __global__ __launch_bounds__(kThreads) void dequant_reduce_kernel(ReduceArgs a)
             int sc[RC];
 #pragma unroll
             for (int i = 0; i < RC; ++i) {
-                const bool on = valid && (r0 + i < a.tp);
+                const bool on = valid && (r0 + i < a.tp) && !(OWN && r0 + i == a.own_rank);
                 const int r = min(r0 + i, a.tp - 1);
                 v[i] = load_codes<E::bits, NTL>((const uint32_t *)a.codes[r], unit, on);
                 sc[i] = on ? (int)ld<NTL>((const uint8_t *)a.scales[r] + unit / G) : sf.sbias;
             }
 #pragma unroll
             for (int i = 0; i < RC; ++i) {
-                if (r0 + i < a.tp) {
+                if (OWN && r0 + i == a.own_rank) {
+                    const u32x4 raw = valid ? ld<NTL>((const u32x4 *)a.own_x + unit)
+                                            : u32x4{0u, 0u, 0u, 0u};
+                    add_raw_bf16(raw, r0 + i == 0, acc);
+                } else if (r0 + i < a.tp) {
                     const int e = sc[i] - sf.sbias;
                     const bool marker = sf.has_nan && sc[i] == 255;
                     poisoned = poisoned || marker;
@@ -648,7 +667,8 @@ __device__ __forceinline__ uint32_t stream_bits_rt(const uint32_t (&s)[NW], int 
 // FUSED: instead of storing the sums, quantize them again in the lane that holds them (same
 // rule as the quantizer applied to binary32 input) and store codes and scales; bit-identical to
 // running the unfused kernels one after the other.
-template <class E, int B, bool OUT_BF16, int RC, bool NTL, bool NTS, bool HW, bool FUSED = false>
+template <class E, int B, bool OUT_BF16, int RC, bool NTL, bool NTS, bool HW, bool FUSED = false,
+          bool OWN = false>
 __global__ __launch_bounds__(kThreads) void dequant_reduce_tile_kernel(ReduceArgs a)
 {
     constexpr int NB = 32 / B;                   // blocks (scales) per chunk
@@ -677,7 +697,7 @@ __global__ __launch_bounds__(kThreads) void dequant_reduce_tile_kernel(ReduceArg
         uint32_t sw[RC];
 #pragma unroll
         for (int i = 0; i < RC; ++i) {
-            const bool on = valid && (r0 + i < a.tp);
+            const bool on = valid && (r0 + i < a.tp) && !(OWN && r0 + i == a.own_rank);
             const int r = min(r0 + i, a.tp - 1);
             const uint32_t *cp = (const uint32_t *)a.codes[r] + chunk * W;
 #pragma unroll
@@ -711,7 +731,15 @@ __global__ __launch_bounds__(kThreads) void dequant_reduce_tile_kernel(ReduceArg
         }
 #pragma unroll
         for (int i = 0; i < RC; ++i) {
-            if (r0 + i < a.tp) {
+            if (OWN && r0 + i == a.own_rank) {
+                // the lane's 32 bfloat16 values: 64 contiguous bytes
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const u32x4 raw = valid ? ld<NTL>((const u32x4 *)a.own_x + chunk * 4 + k)
+                                            : u32x4{0u, 0u, 0u, 0u};
+                    add_raw_bf16(raw, r0 + i == 0, acc + 8 * k);
+                }
+            } else if (r0 + i < a.tp) {
 #pragma unroll
                 for (int n = 0; n < NB; ++n) {
                     const int sc = (int)((sw[i] >> (8 * n)) & 0xFFu);

@@ -24,7 +24,7 @@ def declared_functions():
 def test_header_functions_are_exported(L):
     names = declared_functions()
     assert {"mxc_quantize", "mxc_quantize_batched", "mxc_dequant_reduce", "mxc_requantize_chunk",
-            "mxc_dequant_reduce_requantize", "mxc_packed_sizes", "mxc_strerror", "mxc_copy_probe"} <= set(names)
+            "mxc_dequant_reduce_requantize", "mxc_dequant_reduce_own", "mxc_packed_sizes", "mxc_strerror", "mxc_copy_probe"} <= set(names)
     for n in names:
         assert getattr(L, n) is not None, n
 
@@ -83,6 +83,13 @@ def test_host_side_argument_errors(L):
     assert L.mxc_requantize_chunk(fp, good, 0, 8, 64, 4, 4, good, good, None) == -5
     assert L.mxc_requantize_chunk(fp, good, 0, 8, 64, 4, -1, good, good, None) == -5
     assert L.mxc_requantize_chunk(fp, good, 5, 8, 64, 4, 0, good, good, None) == -7
+    assert L.mxc_dequant_reduce_own(fp, 2, 2, good, arr, arr, 4, 64, good, 0, None) == -5
+    assert L.mxc_dequant_reduce_own(fp, 2, -1, good, arr, arr, 4, 64, good, 0, None) == -5
+    assert L.mxc_dequant_reduce_own(fp, 2, 0, None, arr, arr, 4, 64, good, 0, None) == -1
+    assert L.mxc_dequant_reduce_own(fp, 2, 0, odd, arr, arr, 4, 64, good, 0, None) == -4
+    assert L.mxc_dequant_reduce_own(fp, 2, 0, good, nul, arr, 4, 64, good, 0, None) == -1   # rank 1 NULL
+    nul0 = (vp * 2)(None, good)
+    assert L.mxc_dequant_reduce_own(fp, 2, 0, good, nul0, nul0, 0, 64, good, 0, None) == 0  # own may be NULL
     assert L.mxc_dequant_reduce_requantize(fp, 2, arr, arr, 4, 64, good, None, None) == -1
     assert L.mxc_dequant_reduce_requantize(fp, 2, arr, arr, 4, 64, good, 0x10002, None) == -4
     assert L.mxc_dequant_reduce_requantize(fp, 40, arr, arr, 4, 64, good, good, None) == -5

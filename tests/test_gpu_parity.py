@@ -248,6 +248,32 @@ def test_reduce_keeps_negative_zero_and_order(mxc, oracle_mod):
     assert float(a[0, 0]) == 2.0 ** 24 and float(b[0, 0]) == 2.0 ** 24 + 2
 
 
+@pytest.mark.parametrize("x,y,B", [(2, 1, 32), (2, 2, 32), (3, 2, 32), (2, 1, 8), (1, 1, 16)])
+def test_reduce_with_own_raw_partial(mxc, oracle_mod, x, y, B):
+    """Profiling: N-1 decoded partials plus the worker's own uncompressed one, every own rank;
+    a shape that takes the tile kernel and one (with small blocks) that does not."""
+    for (T, H) in ((12, 1024), (3, 40)) if B == 8 else ((12, 1024),):
+        w = workloads.Workload("own", 5, T, H, seed=77, n_outlier=2, outlier_mult=(20.0, 100.0))
+        fo, fg = oracle_mod.Format(x, y, B, 8), mxc.Format(x, y, B, 8)
+        parts = [workloads.partial_bf16(w, r) for r in range(w.tp)]
+        ocs, oss = oracle_partials(oracle_mod, fo, w)
+        packed = [torch.from_numpy(oracle_mod.pack(fo, c)).cuda() for c in ocs]
+        scales = [torch.from_numpy(s).cuda() for s in oss]
+        for own in range(w.tp):
+            cs = [None if r == own else packed[r] for r in range(w.tp)]
+            ss = [None if r == own else scales[r] for r in range(w.tp)]
+            out = mxc.dequant_reduce_own(fg, own, dev_bf16(parts[own]), cs, ss)
+            out16 = mxc.dequant_reduce_own(fg, own, dev_bf16(parts[own]), packed, scales,
+                                           out_dtype=torch.bfloat16)
+            torch.cuda.synchronize()
+            want = oracle_mod.dequant_reduce_own(fo, own, parts[own],
+                                                 [None if r == own else ocs[r] for r in range(w.tp)],
+                                                 [None if r == own else oss[r] for r in range(w.tp)])
+            assert same_f32(host(out), want)
+            assert np.array_equal(host(out16.view(torch.int16)).view(np.uint16),
+                                  oracle_mod.round_to_bf16(want))
+
+
 @pytest.mark.parametrize("s", [4, 5, 6, 7])
 def test_reduce_narrow_scale_formats(mxc, oracle_mod, s):
     w = workloads.small_like(workloads.CONFIGS[2], 16, 512)

@@ -535,6 +535,33 @@ def test_reduce_order_matters_when_binades_are_far_apart(oracle_mod):
     assert np.all(a == np.float32(2.0 ** 24)) and np.all(b == np.float32(2.0 ** 24 + 2))
 
 
+def test_reduce_with_own_raw_partial_is_the_same_fold_with_one_exact_term(oracle_mod):
+    """Profiling: N-1 decoded partials plus the worker's own raw one.  Checked against a numpy
+    float32 fold, for every choice of the own rank, and against the all-decoded reduction when
+    the own partial happens to be exactly representable."""
+    fmt = oracle_mod.Format(2, 1, 32, 8)
+    w = workloads.Workload("own", 4, 8, 256, 5, n_outlier=2, outlier_mult=(20.0, 100.0))
+    parts = [workloads.partial_bf16(w, r) for r in range(w.tp)]
+    qs = [oracle_mod.quantize_bf16(fmt, p) for p in parts]
+    dec = [oracle_mod.dequantize(fmt, c, s) for c, s in qs]
+    for own in range(w.tp):
+        cs = [None if r == own else qs[r][0] for r in range(w.tp)]
+        ss = [None if r == own else qs[r][1] for r in range(w.tp)]
+        got = oracle_mod.dequant_reduce_own(fmt, own, parts[own], cs, ss)
+        terms = [workloads.bf16_bits_to_f32(parts[r]) if r == own else dec[r] for r in range(w.tp)]
+        acc = terms[0].copy()
+        for d in terms[1:]:
+            acc = (acc + d).astype(np.float32)
+        assert np.array_equal(acc.view(np.uint32), got.view(np.uint32))
+        assert not np.array_equal(got, oracle_mod.dequant_reduce(fmt, [q[0] for q in qs], [q[1] for q in qs]))
+    # a representable own partial (its own decode) gives the all-decoded result
+    rep = workloads.f32_to_bf16_bits(dec[1])
+    assert np.array_equal(workloads.bf16_bits_to_f32(rep), dec[1])
+    a = oracle_mod.dequant_reduce_own(fmt, 1, rep, [q[0] for q in qs], [q[1] for q in qs])
+    b = oracle_mod.dequant_reduce(fmt, [q[0] for q in qs], [q[1] for q in qs])
+    assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
 def test_reduce_starts_from_rank0_value_not_from_zero(oracle_mod):
     fmt = oracle_mod.Format(2, 1, 8, 8)
     negz = np.full((1, 8), 8, np.uint8)          # every code is -0
