@@ -119,7 +119,7 @@ def main():
     stream = torch.cuda.current_stream()
 
     # ---- inputs, resident in HBM -----------------------------------------------------------
-    host_parts = [workloads.partial_bf16(w, r) for r in range(N)]
+    host_parts = workloads.all_partials_bf16(w)
     def upload():
         return [torch.from_numpy(p.view(np.int16)).view(torch.bfloat16).cuda() for p in host_parts]
     x_sets = [upload(), upload()]

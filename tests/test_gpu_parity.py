@@ -403,3 +403,55 @@ def test_full_size_config3_sampled_rows(mxc, oracle_mod):
         cb, sb = mxc.packed_sizes(fg, w.tokens, w.hidden)
         ratio = w.tokens * w.hidden * 2 / (cb + sb)
         assert abs(ratio - 16 / (fo.bits + s / B)) < 1e-9
+
+
+@pytest.mark.parametrize("cfg", [2, 4, 5])
+def test_full_size_other_configs_sampled_rows(mxc, oracle_mod, cfg):
+    """Configurations 2, 4 and 5 at their full sizes, in the launch configuration the benchmark
+    uses (batched quantize, one reduce, per-chunk requantize and the fused form where the
+    configuration names requantization): sampled rows element by element against the oracle,
+    every scale byte against the scale rule, sizes against the closed form."""
+    w = workloads.CONFIGS[cfg]
+    rng = np.random.default_rng(cfg)
+    rows = np.unique(np.concatenate([[0, w.tokens // w.tp - 1, w.tokens // w.tp, w.tokens - 1],
+                                     rng.integers(0, w.tokens, 12)]))
+    parts = workloads.all_partials_bf16(w)
+    xs = [dev_bf16(p) for p in parts]
+    for (x, y, B, s) in w.formats:
+        fo, fg = oracle_mod.Format(x, y, B, s), mxc.Format(x, y, B, s)
+        emax = 2 ** x - 1 - (2 ** (x - 1) - 1)
+        codes, scales = mxc.quantize_batched(fg, xs)
+        out = mxc.dequant_reduce(fg, codes, scales, w.tokens, w.hidden)
+        torch.cuda.synchronize()
+        ocs, oss = [], []
+        for r in range(w.tp):
+            oc, os_ = oracle_mod.quantize_bf16(fo, parts[r][rows])
+            assert np.array_equal(host(scales[r][rows]), os_)
+            assert np.array_equal(host(codes[r][rows]), oracle_mod.pack(fo, oc))
+            ocs.append(oc)
+            oss.append(os_)
+            expf = torch.from_numpy(((parts[r] >> 7) & 0xFF).astype(np.int16)).cuda()
+            blockmax = expf.view(w.tokens, -1, B).max(dim=2).values.to(torch.int32)
+            assert torch.equal(scales[r].to(torch.int32), (blockmax - emax).clamp_(min=0))
+        want = oracle_mod.dequant_reduce(fo, ocs, oss)
+        got = host(out[rows])
+        assert same_f32(got, want)
+        if w.requantize:
+            n_rows = w.tokens // w.tp
+            for c in (0, w.tp - 1, 3):
+                cc, sc = mxc.requantize_chunk(fg, out, w.tp, c)
+                # the fused form on the compressed copies of that chunk
+                cin = [codes[r][c * n_rows:(c + 1) * n_rows] for r in range(w.tp)]
+                sin = [scales[r][c * n_rows:(c + 1) * n_rows] for r in range(w.tp)]
+                cf, sf_ = mxc.dequant_reduce_requantize(fg, cin, sin, n_rows, w.hidden)
+                torch.cuda.synchronize()
+                assert torch.equal(cf, cc) and torch.equal(sf_, sc)
+                sel = rows[(rows >= c * n_rows) & (rows < (c + 1) * n_rows)]
+                if len(sel):
+                    idx = np.searchsorted(rows, sel)
+                    oc, os_ = oracle_mod.quantize_f32(fo, want[idx])
+                    assert np.array_equal(host(sc[sel - c * n_rows]), os_)
+                    assert np.array_equal(host(cc[sel - c * n_rows]), oracle_mod.pack(fo, oc))
+        cb, sb = mxc.packed_sizes(fg, w.tokens, w.hidden)
+        assert abs(w.tokens * w.hidden * 2 / (cb + sb) - 16 / (fo.bits + s / B)) < 1e-9
+        del codes, scales, out

@@ -102,6 +102,14 @@ def partial_bf16(w: Workload, rank: int, rows: Optional[slice] = None) -> np.nda
     return f32_to_bf16_bits(body)
 
 
+def all_partials_bf16(w: Workload, workers: int = 8):
+    """Every rank's partial, drawn in parallel threads (the draws are independent streams, so
+    the result is the same as calling partial_bf16 rank by rank)."""
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=max(1, min(workers, w.tp))) as pool:
+        return list(pool.map(lambda r: partial_bf16(w, r), range(w.tp)))
+
+
 def small_like(w: Workload, tokens: int, hidden: int) -> Workload:
     """The same distribution at a reduced shape (for tests the oracle finishes in seconds)."""
     n_out = max(1, round(w.n_outlier * hidden / w.hidden)) if w.n_outlier else 0
