@@ -272,6 +272,25 @@ def main():
         ms = time_calls(lambda i: wl[i % 3]())
         sweep["requantize_whole_tensor_f32"] = {
             "ms": ms, "hbm_GBps": nb / ms / 1e6, "frac": nb / ms / 1e6 / HBM_PEAK_GBS}
+        # fused dequant-reduce + requantize of one rank's chunk (N compressed chunk copies in, one
+        # compressed chunk out), and of the whole tensor in one launch to show the streaming rate
+        fsets = [packed_set(f) for _ in range(R)]
+        for i in range(R):
+            mxc.quantize_batched(f, x_sets[0], *fsets[i])
+        n_rows = T // N
+        fl = [mxc.prepare_dequant_reduce_requantize(
+                  f, [c[:n_rows] for c in fsets[k][0]], [s_[:n_rows] for s_ in fsets[k][1]],
+                  n_rows, H, cc[0], sc[0]) for k in range(R)]
+        ms = time_calls(lambda i: fl[i % R]())
+        nbf = N * (cb + sb) + cb + sb
+        sweep["fused_reduce_requantize_one_chunk"] = {
+            "ms": ms, "hbm_GBps": nbf / ms / 1e6, "frac": nbf / ms / 1e6 / HBM_PEAK_GBS}
+        fw = [mxc.prepare_dequant_reduce_requantize(f, fsets[k][0], fsets[k][1], T, H, cw[k], sw[k])
+              for k in range(R)]
+        ms = time_calls(lambda i: fw[i % R]())
+        nbw = N * (cbw + sbw) + cbw + sbw
+        sweep["fused_reduce_requantize_whole_tensor"] = {
+            "ms": ms, "hbm_GBps": nbw / ms / 1e6, "frac": nbw / ms / 1e6 / HBM_PEAK_GBS}
         result["sweep"] = sweep
 
     if not args.no_cpu_baseline:

@@ -131,8 +131,8 @@ int launch_fused(const ReduceArgs &a, hipStream_t st)
 {
     const size_t chunks = a.units / 4;
     const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads));
-    hipLaunchKernelGGL((dequant_reduce_tile_kernel<E, B, false, tile_rc<E>(), kReduceNTL, kQuantNTS,
-                                                   kHw, true>),
+    // no LDS tile and a read-dominated stream: all eight ranks' loads in flight at once
+    hipLaunchKernelGGL((dequant_reduce_tile_kernel<E, B, false, 8, kReduceNTL, kQuantNTS, kHw, true>),
                        grid, dim3(kThreads), 0, st, a);
     return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_HIP;
 }

@@ -371,6 +371,61 @@ def test_requantize_f32_rounding_corners(mxc, oracle_mod):
         assert np.array_equal(got, oc), np.argwhere(got != oc)[:5]
 
 
+# ------------------------------------------------------------------------ HIP graphs --------
+
+def test_calls_can_be_captured_in_a_hip_graph(mxc, oracle_mod):
+    """The library allocates nothing and never synchronises, so a step (quantize all partials,
+    reduce, requantize a chunk, fused form) can be recorded into a HIP graph.  The graph is
+    replayed several times on fresh inputs, with eager work and synchronisations in between, and
+    every replay is checked against the oracle."""
+    w = workloads.small_like(workloads.CONFIGS[2], 64, 1024)
+    fo, fg = oracle_mod.Format(2, 2, 32, 8), mxc.Format(2, 2, 32, 8)
+    T, H, N = w.tokens, w.hidden, w.tp
+    xs = [torch.zeros((T, H), dtype=torch.bfloat16, device="cuda") for _ in range(N)]
+    cb, sb = mxc.packed_sizes(fg, T, H)
+    codes = [torch.zeros((T, cb // T), dtype=torch.uint8, device="cuda") for _ in range(N)]
+    scales = [torch.zeros((T, sb // T), dtype=torch.uint8, device="cuda") for _ in range(N)]
+    out = torch.zeros((T, H), dtype=torch.float32, device="cuda")
+    cbc, sbc = mxc.packed_sizes(fg, T // N, H)
+    cc = torch.zeros(cbc, dtype=torch.uint8, device="cuda")
+    sc = torch.zeros(sbc, dtype=torch.uint8, device="cuda")
+    cf = torch.zeros(cb, dtype=torch.uint8, device="cuda")
+    sf_ = torch.zeros(sb, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        mxc.quantize_batched(fg, xs, codes, scales)
+        mxc.dequant_reduce(fg, codes, scales, T, H, out=out)
+        mxc.requantize_chunk(fg, out, N, 1, cc, sc)
+        mxc.dequant_reduce_requantize(fg, codes, scales, T, H, cf, sf_)
+    for replay in range(4):
+        ww = workloads.Workload("graph", N, T, H, seed=300 + replay, n_outlier=3,
+                                outlier_mult=(20.0, 100.0))
+        parts = [workloads.partial_bf16(ww, r) for r in range(N)]
+        for r in range(N):
+            xs[r].copy_(dev_bf16(parts[r]))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ocs, oss = zip(*[oracle_mod.quantize_bf16(fo, p) for p in parts])
+        want = oracle_mod.dequant_reduce(fo, list(ocs), list(oss))
+        assert same_f32(host(out), want)
+        for r in range(N):
+            assert np.array_equal(host(scales[r]), oss[r])
+            assert np.array_equal(host(codes[r]), oracle_mod.pack(fo, ocs[r]))
+        rows = T // N
+        oc, os_ = oracle_mod.quantize_f32(fo, want[rows:2 * rows])
+        assert np.array_equal(host(sc).reshape(rows, -1), os_)
+        assert np.array_equal(host(cc).reshape(rows, -1), oracle_mod.pack(fo, oc))
+        oc, os_ = oracle_mod.quantize_f32(fo, want)
+        assert np.array_equal(host(sf_).reshape(T, -1), os_)
+        assert np.array_equal(host(cf).reshape(T, -1), oracle_mod.pack(fo, oc))
+        # eager work between replays
+        eager = mxc.dequant_reduce(fg, codes, scales, T, H)
+        torch.cuda.synchronize()
+        assert torch.equal(eager, out)
+
+
 # ------------------------------------------------------------------------ full size ---------
 
 def test_full_size_config3_sampled_rows(mxc, oracle_mod):
