@@ -48,9 +48,12 @@ constexpr bool kQuantNTL = true, kQuantNTS = true;
 constexpr int kReduceU = 4;         // units per lane, dequant-reduce
 constexpr int kReduceRC = 8;        // ranks loaded together, unit form
 constexpr bool kReduceNTL = true, kReduceNTS = false;
-// ranks loaded together, tile form: 4 for one 128-bit load per rank, 2 when a chunk's codes take
-// several narrower loads
-template <class E> constexpr int tile_rc() { return E::bits == 4 ? 4 : 2; }
+// ranks loaded together, tile form (measured): 4 where decoding is cheap (one 128-bit load and
+// FP4 conversions, or the whole-chunk BF6 conversion), 2 otherwise
+template <class E> constexpr int tile_rc()
+{
+    return (E::bits == 4 || (E::x == 3 && E::y == 2)) ? 4 : 2;
+}
 constexpr int kCopyU = 1;
 constexpr bool kHw = true;          // use the scaled-conversion instructions where exact
 

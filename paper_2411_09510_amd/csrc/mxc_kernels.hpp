@@ -30,6 +30,9 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x32 __attribute__((ext_vector_type(32)));
+typedef uint32_t u32x6 __attribute__((ext_vector_type(6)));
 
 enum HwKind { HW_NONE = 0, HW_FP4 = 1, HW_BF8 = 2, HW_FP8 = 3 };
 
@@ -675,6 +678,7 @@ __global__ __launch_bounds__(kThreads) void dequant_reduce_tile_kernel(ReduceArg
     constexpr int W = E::bits;                   // dwords of codes per chunk
     constexpr bool kHw = HW && E::hw != HW_NONE;
     constexpr int OC = OUT_BF16 ? 4 : 8;         // 16-byte output pieces per lane
+    constexpr bool kChunkBf6 = E::x == 3 && E::y == 2 && B == 32;   // chunk = one hardware BF6 block
     __shared__ u32x4 tile[kThreads / 64][FUSED ? 1 : 64 * OC];
 
     const int lane = (int)(threadIdx.x & 63);
@@ -745,10 +749,22 @@ __global__ __launch_bounds__(kThreads) void dequant_reduce_tile_kernel(ReduceArg
                     const int sc = (int)((sw[i] >> (8 * n)) & 0xFFu);
                     const int e = sc - sf.sbias;
                     poisoned[n] = poisoned[n] || (sf.has_nan && sc == 255);
-                    const int field = e - E::beta + E::hw_bias + 127;
+                    const int field = kChunkBf6 ? e + 127 : e - E::beta + E::hw_bias + 127;
                     const bool ok = field >= 0 && field <= 254;
                     float d[B];
-                    if (kHw && __builtin_amdgcn_ballot_w64(!ok) == 0) {
+                    if (kHw && kChunkBf6 && __builtin_amdgcn_ballot_w64(!ok) == 0) {
+                        // E3M2 is the hardware's 6-bit BF6 and the lane holds one whole block:
+                        // a single instruction decodes the 32 codes
+                        const u32x6 src = {cw[i][0], cw[i][1], cw[i][2], cw[i][3 < W ? 3 : 0],
+                                           cw[i][4 < W ? 4 : 0], cw[i][5 < W ? 5 : 0]};
+                        // inline assembly with an early-clobber result, for the reason given at
+                        // the matching encode below (result registers must not overlap the scale)
+                        f32x32 r;
+                        const float hs6 = __uint_as_float((uint32_t)field << 23);
+                        asm("v_cvt_scalef32_pk32_f32_bf6 %0, %1, %2" : "=&v"(r) : "v"(src), "v"(hs6));
+#pragma unroll
+                        for (int j = 0; j < B; ++j) d[j] = r[j < 32 ? j : 0];
+                    } else if (kHw && __builtin_amdgcn_ballot_w64(!ok) == 0) {
                         const float hs = __uint_as_float((uint32_t)field << 23);
                         // B codes of block n, eight at a time
 #pragma unroll
@@ -800,6 +816,35 @@ __global__ __launch_bounds__(kThreads) void dequant_reduce_tile_kernel(ReduceArg
             for (int j = 0; j < B; ++j) m = max(m, __float_as_uint(acc[n * B + j]) & 0x7FFFFFFFu);
             const int expfield = (int)(m >> 23);
             int sc = 0;
+            if (kHw && kChunkBf6) {
+                // one instruction rounds the lane's 32 sums to BF6 = E3M2 (same scale rule)
+                const int unclamped = expfield - 127 - E::emax + sf.sbias;
+                const bool finite = expfield != 255;
+                sc = finite ? min(max(unclamped, 0), sf.smax) : sf.nonfinite;
+                const int fld = sc - sf.sbias + 127;
+                if (__builtin_amdgcn_ballot_w64(finite && (fld < 0 || fld > 254)) == 0) {
+                    // the instruction interleaves its two sources: result code 2j comes from
+                    // the first operand's element j, code 2j+1 from the second operand's
+                    f32x16 even, odd;
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) {
+                        even[j] = acc[2 * j];
+                        odd[j] = acc[2 * j + 1];
+                    }
+                    // Issued as inline assembly with an early-clobber result: through the builtin
+                    // the register allocator let the six result registers overlap the per-lane
+                    // scale register, and every code after the first two came out wrong.
+                    u32x6 q;
+                    const float hs = __uint_as_float((uint32_t)max(fld, 0) << 23);
+                    asm("v_cvt_scalef32_2xpk16_bf6_f32 %0, %1, %2, %3"
+                        : "=&v"(q)
+                        : "v"(even), "v"(odd), "v"(hs));
+#pragma unroll
+                    for (int k = 0; k < W; ++k) cw[k] = finite ? q[k < 6 ? k : 0] : 0u;
+                    sbytes |= (uint32_t)sc << (8 * n);
+                    continue;
+                }
+            }
 #pragma unroll
             for (int g = 0; g < B / 8; ++g) {
                 const int first = n * B + g * 8;

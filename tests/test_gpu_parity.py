@@ -341,6 +341,35 @@ def test_fused_reduce_requantize_equals_unfused_pair(mxc, oracle_mod, x, y, B):
         assert np.array_equal(host(cf), oracle_mod.pack(fo, oc))
 
 
+@pytest.mark.parametrize("s", [4, 5, 7])
+def test_fused_and_requantize_with_narrow_scales(mxc, oracle_mod, s):
+    """Narrow scale formats clamp at both ends: sums far above the range saturate, far below
+    round to zero, in the fused form and in requantize alike."""
+    rng = np.random.default_rng(s)
+    T, H, tp = 8, 1024, 4
+    for (x, y, B) in ((3, 2, 32), (2, 1, 32), (2, 2, 16)):
+        fo, fg = oracle_mod.Format(x, y, B, s), mxc.Format(x, y, B, s)
+        top = 2 ** s - 1
+        ocs = [rng.integers(0, 2 ** fo.bits, size=(T, H), dtype=np.uint8) for _ in range(tp)]
+        oss = [rng.integers(0, top + 1, size=(T, H // B), dtype=np.uint8) for _ in range(tp)]
+        packed = [torch.from_numpy(oracle_mod.pack(fo, c)).cuda() for c in ocs]
+        scales = [torch.from_numpy(v).cuda() for v in oss]
+        red = mxc.dequant_reduce(fg, packed, scales, T, H)
+        # stretch the reduced tensor far outside the scale range for the requantize check
+        wide = red.clone()
+        wide[1] *= 2.0 ** 60
+        wide[2] *= 2.0 ** -60
+        c2, s2 = mxc.requantize_chunk(fg, wide, 1, 0)
+        cf, sf_ = mxc.dequant_reduce_requantize(fg, packed, scales, T, H)
+        torch.cuda.synchronize()
+        want = oracle_mod.dequant_reduce(fo, ocs, oss)
+        assert same_f32(host(red), want)
+        oc, os_ = oracle_mod.quantize_f32(fo, want)
+        assert np.array_equal(host(sf_), os_) and np.array_equal(host(cf), oracle_mod.pack(fo, oc))
+        oc, os_ = oracle_mod.quantize_f32(fo, host(wide))
+        assert np.array_equal(host(s2), os_) and np.array_equal(host(c2), oracle_mod.pack(fo, oc))
+
+
 def test_requantize_f32_rounding_corners(mxc, oracle_mod):
     """binary32 inputs a hair around rounding midpoints, which need all 24 significand bits."""
     rng = np.random.default_rng(21)
