@@ -238,8 +238,18 @@ def main():
             ql, dl = make_launches(f, ps)
             qms = time_calls(lambda i: ql[i % PERIOD]())
             rms = time_calls(lambda i: dl[i % PERIOD]())
+            # quality proxy on the synthetic tensors (the paper's perplexity tables need models
+            # and data): error of the reduced output against the uncompressed sum, plain torch
+            dl[0]()
+            exact = x_sets[0][0].float()
+            for r in range(1, N):
+                exact += x_sets[0][r].float()
+            err = (outs[0] - exact).double()
+            sqnr = 10.0 * float(torch.log10(exact.double().pow(2).sum() / err.pow(2).sum()))
+            del exact, err
             sweep[f"e{fx}m{fy}_b{fb}"] = {
                 "compression_ratio": 16 / mxc.effective_bits(f),
+                "reduced_output_sqnr_db": sqnr,
                 "quantize": {"ms": qms, "GBps_bf16": bf16_bytes / qms / 1e6,
                              "hbm_GBps": qb / qms / 1e6, "frac": qb / qms / 1e6 / HBM_PEAK_GBS,
                              "frac_of_copy": qb / qms / 1e6 / copy_gbs},
