@@ -496,14 +496,17 @@ struct ReduceArgs {
     ScaleFmt sf;
 };
 
-// Adds (or, for the first rank, assigns) eight bfloat16 values, given as four dwords, to acc.
-__device__ __forceinline__ void add_raw_bf16(const u32x4 v, bool first, float *acc)
+// The accumulators start at -0.0: x + (-0.0) is x for every x (including +0, -0 and NaN), so
+// adding rank 0's value to it is the same as starting the fold from that value.
+constexpr float kFoldStart = -0.0f;
+
+// Adds eight bfloat16 values, given as four dwords, to acc.
+__device__ __forceinline__ void add_raw_bf16(const u32x4 v, float *acc)
 {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const float lo = __uint_as_float(v[j] << 16), hi = __uint_as_float(v[j] & 0xFFFF0000u);
-        acc[2 * j] = first ? lo : acc[2 * j] + lo;
-        acc[2 * j + 1] = first ? hi : acc[2 * j + 1] + hi;
+        acc[2 * j] += __uint_as_float(v[j] << 16);
+        acc[2 * j + 1] += __uint_as_float(v[j] & 0xFFFF0000u);
     }
 }
 
@@ -588,7 +591,9 @@ __global__ __launch_bounds__(kThreads) void dequant_reduce_kernel(ReduceArgs a)
     for (int u = 0; u < U; ++u) {
         const size_t unit = wave_base + (size_t)(u * 64 + lane);
         const bool valid = unit < a.units;
-        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        float acc[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = kFoldStart;
         bool poisoned = false;                   // some rank marked this block non-finite
         for (int r0 = 0; r0 < a.tp; r0 += RC) {
             uint64_t v[RC];
@@ -605,7 +610,7 @@ __global__ __launch_bounds__(kThreads) void dequant_reduce_kernel(ReduceArgs a)
                 if (OWN && r0 + i == a.own_rank) {
                     const u32x4 raw = valid ? ld<NTL>((const u32x4 *)a.own_x + unit)
                                             : u32x4{0u, 0u, 0u, 0u};
-                    add_raw_bf16(raw, r0 + i == 0, acc);
+                    add_raw_bf16(raw, acc);
                 } else if (r0 + i < a.tp) {
                     const int e = sc[i] - sf.sbias;
                     const bool marker = sf.has_nan && sc[i] == 255;
@@ -622,7 +627,7 @@ __global__ __launch_bounds__(kThreads) void dequant_reduce_kernel(ReduceArgs a)
                         for (int j = 0; j < 8; ++j) d[j] = decode<E>(v[i], j, e + 127 - E::beta);
                     }
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) acc[j] = (r0 + i == 0) ? d[j] : acc[j] + d[j];
+                    for (int j = 0; j < 8; ++j) acc[j] += d[j];
                 }
             }
         }
@@ -691,7 +696,7 @@ __global__ __launch_bounds__(kThreads) void dequant_reduce_tile_kernel(ReduceArg
 
     float acc[32];
 #pragma unroll
-    for (int j = 0; j < 32; ++j) acc[j] = 0.f;
+    for (int j = 0; j < 32; ++j) acc[j] = kFoldStart;
     bool poisoned[NB];
 #pragma unroll
     for (int n = 0; n < NB; ++n) poisoned[n] = false;
@@ -741,7 +746,7 @@ __global__ __launch_bounds__(kThreads) void dequant_reduce_tile_kernel(ReduceArg
                 for (int k = 0; k < 4; ++k) {
                     const u32x4 raw = valid ? ld<NTL>((const u32x4 *)a.own_x + chunk * 4 + k)
                                             : u32x4{0u, 0u, 0u, 0u};
-                    add_raw_bf16(raw, r0 + i == 0, acc + 8 * k);
+                    add_raw_bf16(raw, acc + 8 * k);
                 }
             } else if (r0 + i < a.tp) {
 #pragma unroll
@@ -790,8 +795,7 @@ __global__ __launch_bounds__(kThreads) void dequant_reduce_tile_kernel(ReduceArg
                         }
                     }
 #pragma unroll
-                    for (int j = 0; j < B; ++j)
-                        acc[n * B + j] = (r0 + i == 0) ? d[j] : acc[n * B + j] + d[j];
+                    for (int j = 0; j < B; ++j) acc[n * B + j] += d[j];
                 }
             }
         }
