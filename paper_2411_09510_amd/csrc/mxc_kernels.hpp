@@ -144,7 +144,7 @@ __device__ __forceinline__ uint32_t round_full_sig(float v, int neg_e)
 }
 
 // ---------------------------------------------------------------------------------------------
-// Four b-bit codes <-> four bytes of a dword (code k in byte k).
+// Four bytes of a dword (code k in byte k, each below 2^b) -> four b-bit fields.
 template <int BITS>
 __device__ __forceinline__ uint32_t squeeze4(uint32_t bytes)
 {
@@ -152,14 +152,6 @@ __device__ __forceinline__ uint32_t squeeze4(uint32_t bytes)
     // bytes 0,1 -> 2b bits in the low half, bytes 2,3 -> 2b bits in the high half
     uint32_t t = (bytes & (m1 * 0x00010001u)) | ((bytes >> (8 - BITS)) & ((m1 << BITS) * 0x00010001u));
     return (t & m2) | ((t >> (16 - 2 * BITS)) & (m2 << 2 * BITS));
-}
-
-template <int BITS>
-__device__ __forceinline__ uint32_t spread4(uint32_t fields)
-{
-    constexpr uint32_t m1 = (1u << BITS) - 1u, m2 = (1u << 2 * BITS) - 1u;
-    uint32_t t = (fields & m2) | ((fields << (16 - 2 * BITS)) & (m2 << 16));
-    return (t & (m1 * 0x00010001u)) | ((t << (8 - BITS)) & (m1 * 0x01000100u));
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -534,12 +526,26 @@ __device__ __forceinline__ f32x2 cvt_8bit_pair(uint32_t v, float s)
                          : __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(v, s, HI);
 }
 
-// Four squeezed b-bit codes -> four bytes sign<<7 | magnitude.
+// (a & m) | (b & ~m): one v_bfi / v_bitop3.
+__device__ __forceinline__ uint32_t bitselect(uint32_t m, uint32_t a, uint32_t b)
+{
+    return (a & m) | (b & ~m);
+}
+
+// Four b-bit codes in the low 4b bits of f (bits above are ignored) -> four bytes
+// sign<<7 | magnitude.  Copy k of f, shifted left by k*(8-b), carries code k's magnitude at byte k
+// and code k-1's sign at bit 7 of byte k-1; four selects stitch the copies together and one mask
+// clears what lies between magnitude and sign.
 template <class E>
 __device__ __forceinline__ uint32_t codes_to_bytes(uint32_t f)
 {
-    uint32_t b = spread4<E::bits>(f);
-    return (b & (E::magmask * 0x01010101u)) | ((b << (7 - E::x - E::y)) & 0x80808080u);
+    constexpr int b = E::bits, g = 8 - E::bits;
+    uint32_t r = f;
+    r = bitselect((1u << (b - 1)) - 1u, r, f << g);
+    r = bitselect((1u << (8 + b - 1)) - 1u, r, f << (2 * g));
+    r = bitselect((1u << (16 + b - 1)) - 1u, r, f << (3 * g));
+    r = bitselect((1u << (24 + b - 1)) - 1u, r, f << (4 * g));
+    return r & ((E::magmask | 0x80u) * 0x01010101u);
 }
 
 // Eight codes -> eight binary32 values times the power of two in hw_scale's exponent field.
@@ -554,9 +560,8 @@ __device__ __forceinline__ void decode_unit_hw(uint64_t v, float hw_scale, float
         r3 = cvt_fp4_pair<3>((uint32_t)v, hw_scale);
     } else {
         constexpr int K = E::hw == HW_BF8 ? HW_BF8 : HW_FP8;
-        constexpr uint32_t m4 = (1u << 4 * E::bits) - 1u;
-        const uint32_t b0 = codes_to_bytes<E>((uint32_t)v & m4);
-        const uint32_t b1 = codes_to_bytes<E>((uint32_t)(v >> (4 * E::bits)) & m4);
+        const uint32_t b0 = codes_to_bytes<E>((uint32_t)v);
+        const uint32_t b1 = codes_to_bytes<E>((uint32_t)(v >> (4 * E::bits)));
         r0 = cvt_8bit_pair<K, false>(b0, hw_scale);
         r1 = cvt_8bit_pair<K, true>(b0, hw_scale);
         r2 = cvt_8bit_pair<K, false>(b1, hw_scale);

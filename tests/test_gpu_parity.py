@@ -204,6 +204,47 @@ def test_reduce_config1_all_formats(mxc, oracle_mod, x, y, B):
     check_reduce(mxc, oracle_mod, fo, fg, cs, ss, w.tokens, w.hidden)
 
 
+def test_reduce_and_fused_do_not_write_past_the_end(mxc, oracle_mod):
+    """Canaries behind every output of the reduce kernels (f32, bf16, own-raw, fused, and the
+    unit form used for sizes that are not a multiple of 32), on ragged sizes."""
+    rng = np.random.default_rng(4)
+    for (x, y, B, T, H) in ((2, 1, 32, 3, 96), (2, 2, 32, 5, 2080), (3, 2, 32, 1, 32), (2, 1, 8, 3, 40),
+                            (3, 2, 16, 7, 48), (1, 1, 8, 1, 8)):
+        fo, fg = oracle_mod.Format(x, y, B, 8), mxc.Format(x, y, B, 8)
+        tp = 3
+        ocs = [rng.integers(0, 2 ** fo.bits, size=(T, H), dtype=np.uint8) for _ in range(tp)]
+        oss = [rng.integers(100, 150, size=(T, H // B), dtype=np.uint8) for _ in range(tp)]
+        packed = [torch.from_numpy(oracle_mod.pack(fo, c)).cuda() for c in ocs]
+        scales = [torch.from_numpy(v).cuda() for v in oss]
+        n = T * H
+        want = oracle_mod.dequant_reduce(fo, ocs, oss)
+        for dt in (torch.float32, torch.bfloat16):
+            buf = torch.full((n + 64,), 7.0, dtype=dt, device="cuda")
+            mxc.dequant_reduce(fg, packed, scales, T, H, out=buf[:n].view(T, H))
+            torch.cuda.synchronize()
+            assert (buf[n:] == 7.0).all()
+            if dt == torch.float32:
+                assert same_f32(host(buf[:n]).reshape(T, H), want)
+        own = dev_bf16(workloads.f32_to_bf16_bits(rng.standard_normal((T, H)).astype(np.float32)))
+        buf = torch.full((n + 64,), 7.0, dtype=torch.float32, device="cuda")
+        mxc.dequant_reduce_own(fg, 1, own, packed, scales, out=buf[:n].view(T, H))
+        torch.cuda.synchronize()
+        assert (buf[n:] == 7.0).all()
+        if n % 32 == 0:
+            cb, sb = mxc.packed_sizes(fg, T, H)
+            cbuf = torch.full((cb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+            sbuf = torch.full((sb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+            mxc.dequant_reduce_requantize(fg, packed, scales, T, H, cbuf[:cb], sbuf[:sb])
+            torch.cuda.synchronize()
+            assert (cbuf[cb:] == 0xA5).all() and (sbuf[sb:] == 0xA5).all()
+            oc, os_ = oracle_mod.quantize_f32(fo, want)
+            assert np.array_equal(host(sbuf[:sb]).reshape(T, -1), os_)
+            assert np.array_equal(host(cbuf[:cb]).reshape(T, -1), oracle_mod.pack(fo, oc))
+        else:
+            with pytest.raises(mxc.MxcError):
+                mxc.dequant_reduce_requantize(fg, packed, scales, T, H)
+
+
 @pytest.mark.parametrize("tp", [1, 2, 3, 4, 7, 8, 9, 16, 17, 32])
 def test_reduce_any_tp(mxc, oracle_mod, tp):
     w = workloads.Workload("tp", tp, 9, 1056, seed=40 + tp, n_outlier=3, outlier_mult=(20.0, 100.0))
