@@ -301,6 +301,37 @@ def main():
         nbw = N * (cbw + sbw) + cbw + sbw
         sweep["fused_reduce_requantize_whole_tensor"] = {
             "ms": ms, "hbm_GBps": nbw / ms / 1e6, "frac": nbw / ms / 1e6 / HBM_PEAK_GBS}
+        # the paper's own profiled input sizes are a few hundred tokens (Table 3: 2x64 ... 16x256):
+        # one rank's quantize and the N-way reduce at 256 tokens, where a call is launch-bound
+        f = mxc.Format(2, 1, 32, 8)
+        Ts = 256
+        xs_small = [x_sets[0][r][:Ts] for r in range(N)]
+        cbs, sbs = mxc.packed_sizes(f, Ts, H)
+        cs_small = [torch.empty((Ts, cbs // Ts), dtype=torch.uint8, device="cuda") for _ in range(N)]
+        ss_small = [torch.empty((Ts, sbs // Ts), dtype=torch.uint8, device="cuda") for _ in range(N)]
+        out_small = torch.empty((Ts, H), dtype=torch.float32, device="cuda")
+        q1 = mxc.prepare_quantize_batched(f, xs_small[:1], cs_small[:1], ss_small[:1])
+        qn = mxc.prepare_quantize_batched(f, xs_small, cs_small, ss_small)
+        rn = mxc.prepare_dequant_reduce(f, cs_small, ss_small, Ts, H, out_small)
+        qn()
+        def small_step(i):
+            qn()
+            rn()
+        eager_us = time_calls(small_step) * 1e3
+        # the same step recorded once into a HIP graph and replayed (the library never allocates
+        # or synchronises, so its calls can be captured)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _ in range(10):
+                small_step(0)
+        graph_us = time_calls(lambda i: graph.replay(), n=20, warm=20) * 1e3 / 10
+        sweep["paper_sized_256_tokens_e2m1"] = {
+            "quantize_one_partial_us": time_calls(lambda i: q1()) * 1e3,
+            "dequant_reduce_%d_partials_us" % N: time_calls(lambda i: rn()) * 1e3,
+            "step_quantize_%d_plus_reduce_eager_us" % N: eager_us,
+            "step_quantize_%d_plus_reduce_graph_replay_us" % N: graph_us,
+        }
         result["sweep"] = sweep
 
     if not args.no_cpu_baseline:

@@ -33,7 +33,8 @@ ScaleFmt scale_fmt(const mxc_format *f)
 int shape_units(const mxc_format *f, int64_t tokens, int64_t hidden, size_t *units)
 {
     if (tokens < 0 || hidden <= 0 || hidden % f->block) return MXC_ERR_SHAPE;
-    if (tokens > 0 && hidden > (int64_t)((1ull << 46) / (uint64_t)tokens)) return MXC_ERR_SHAPE;
+    // 2^40 elements at most: keeps every byte offset in 64 bits and every grid below 2^31 groups
+    if (tokens > 0 && hidden > (int64_t)((1ull << 40) / (uint64_t)tokens)) return MXC_ERR_SHAPE;
     *units = (size_t)tokens * (size_t)hidden / 8;
     return MXC_OK;
 }

@@ -61,6 +61,7 @@ def test_host_side_argument_errors(L):
     assert L.mxc_quantize(None, good, 4, 64, good, good, None) == -1
     assert L.mxc_quantize(fp, good, 4, 48, good, good, None) == -3
     assert L.mxc_quantize(fp, good, -1, 64, good, good, None) == -3
+    assert L.mxc_quantize(fp, good, 1 << 30, 1 << 20, good, good, None) == -3      # too large
     assert L.mxc_quantize(fp, odd, 4, 64, good, good, None) == -4
     assert L.mxc_quantize(fp, good, 4, 64, odd, good, None) == -4
     assert L.mxc_quantize(fp, good, 4, 64, good, 0x10001, None) == -4

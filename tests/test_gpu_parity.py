@@ -441,6 +441,38 @@ def test_requantize_f32_rounding_corners(mxc, oracle_mod):
         assert np.array_equal(got, oc), np.argwhere(got != oc)[:5]
 
 
+# ------------------------------------------------------------------------ streams -----------
+
+def test_calls_run_on_the_stream_they_are_given(mxc, oracle_mod):
+    """Two independent pipelines issued on two non-default streams at once; each call passes its
+    stream explicitly.  Results must be those of the oracle for both."""
+    fo, fg = oracle_mod.Format(2, 1, 32, 8), mxc.Format(2, 1, 32, 8)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    jobs = []
+    for k, st in enumerate(streams):
+        w = workloads.Workload("streams", 4, 96, 4096, seed=500 + k, n_outlier=4,
+                               outlier_mult=(20.0, 100.0))
+        parts = [workloads.partial_bf16(w, r) for r in range(w.tp)]
+        xs = [dev_bf16(p) for p in parts]
+        jobs.append((w, parts, xs, st))
+    torch.cuda.synchronize()
+    outs = []
+    for rep in range(3):
+        for (w, parts, xs, st) in jobs:
+            codes, scales = mxc.quantize_batched(fg, xs, stream=st)
+            with torch.cuda.stream(st):
+                out = torch.empty((w.tokens, w.hidden), dtype=torch.float32, device="cuda")
+            mxc.dequant_reduce(fg, codes, scales, w.tokens, w.hidden, out=out, stream=st)
+            outs.append((w, parts, out, codes, scales))
+    for st in streams:
+        st.synchronize()
+    for (w, parts, out, codes, scales) in outs:
+        ocs, oss = zip(*[oracle_mod.quantize_bf16(fo, p) for p in parts])
+        assert same_f32(host(out), oracle_mod.dequant_reduce(fo, list(ocs), list(oss)))
+        for r in range(w.tp):
+            assert np.array_equal(host(scales[r]), oss[r])
+
+
 # ------------------------------------------------------------------------ HIP graphs --------
 
 def test_calls_can_be_captured_in_a_hip_graph(mxc, oracle_mod):
