@@ -11,7 +11,9 @@ So that no kernel reads data another kernel has just left in the 256 MB last-lev
 packed buffers rotate over three sets (a step quantizes into one set and reduces the set that
 was written two steps earlier) and the bf16 inputs alternate between two copies.
 
-Prints ONE JSON line; see the design doc for the fields `roofline` and `cpu_baseline`.
+Prints ONE JSON line.  `roofline` is for the kernel that takes most of the step: achieved =
+algorithmic bytes per launch / average launch duration (HIP events on the launch stream), against
+the 8 TB/s HBM peak; `cpu_baseline` is the CPU oracle timed on the same workload, for context.
 """
 from __future__ import annotations
 

@@ -46,6 +46,15 @@ class Format:
         return _CFormat(self.ebits, self.mbits, self.block, self.scale_bits)
 
 
+def int_format(bits: int, block: int = 32, scale_bits: int = 8) -> Format:
+    """INT3 / INT4 / INT5 of the paper's parameter list: a symmetric sign-magnitude integer grid
+    is the 1-bit-exponent float E1M(bits-2) (its ablation table prints identical results for the
+    two), so the integer types are served by that format."""
+    if bits not in (3, 4, 5, 6):
+        raise ValueError("integer element types of 3 to 6 bits only")
+    return Format(1, bits - 2, block, scale_bits)
+
+
 _lib: Optional[ctypes.CDLL] = None
 
 

@@ -110,3 +110,17 @@ def test_binding_refuses_host_tensors():
     import paper_2411_09510_amd as mxc
     with pytest.raises(ValueError):
         mxc.quantize(mxc.Format(2, 1), torch.zeros(4, 64, dtype=torch.bfloat16))
+
+
+def test_integer_types_are_one_bit_exponent_floats(oracle_mod):
+    """INT3/4/5 (Method, parameter list) = E1M1/E1M2/E1M3: a uniform symmetric grid."""
+    import paper_2411_09510_amd as mxc
+    for k in (3, 4, 5):
+        f = mxc.int_format(k, 16, 5)
+        assert (f.ebits, f.mbits, f.block, f.scale_bits) == (1, k - 2, 16, 5) and f.bits == k
+        fo = oracle_mod.Format(f.ebits, f.mbits, f.block, f.scale_bits)
+        vals = [oracle_mod.code_value(fo, c) for c in range(2 ** (k - 1))]
+        assert vals == [c * vals[1] for c in range(2 ** (k - 1))]       # uniform grid
+        assert mxc.effective_bits(f) == k + 5 / 16
+    with pytest.raises(ValueError):
+        mxc.int_format(8)
