@@ -48,7 +48,9 @@ constexpr int kQuantU32 = 1;        // units per lane, quantize from binary32 (L
 constexpr bool kQuantNTL = true, kQuantNTS = true;
 constexpr int kReduceU = 4;         // units per lane, dequant-reduce
 constexpr int kReduceRC = 8;        // ranks loaded together, unit form
-constexpr bool kReduceNTL = true;   // stores: see kKeepOutputBytes
+// nontemporal stores: measured 5 % faster than plain ones whenever the outputs of successive
+// calls do not all fit the 256 MB last-level cache
+constexpr bool kReduceNTL = true, kReduceNTS = true;
 // ranks loaded together, tile form (measured): 4 where decoding is cheap (one 128-bit load and
 // FP4 conversions, or the whole-chunk BF6 conversion), 2 otherwise
 template <class E> constexpr int tile_rc()
@@ -100,37 +102,24 @@ int quantize_by_format(const mxc_format *f, const QuantArgs &a, int n, hipStream
     }
 }
 
-// An output of up to this many bytes is written with plain stores, which leave it in the 256 MB
-// last-level cache for whatever consumes it next; a larger one is streamed with nontemporal
-// stores (measured: plain stores win by 7 % at 128 MiB, nontemporal ones by 5-6 % from 256 MiB).
-constexpr size_t kKeepOutputBytes = (size_t)160 << 20;
-
-template <class E, int B, bool OUT_BF16, bool OWN, bool NTS>
-int launch_reduce_nts(const ReduceArgs &a, hipStream_t st)
+template <class E, int B, bool OUT_BF16, bool OWN>
+int launch_reduce_as(const ReduceArgs &a, hipStream_t st)
 {
     if (a.units % 4 == 0) {
         // whole 32-element chunks: one lane per chunk, output staged through LDS
         const size_t chunks = a.units / 4;
         const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads));
         hipLaunchKernelGGL((dequant_reduce_tile_kernel<E, B, OUT_BF16, tile_rc<E>(), kReduceNTL,
-                                                       NTS, kHw, false, OWN>),
+                                                       kReduceNTS, kHw, false, OWN>),
                            grid, dim3(kThreads), 0, st, a);
     } else {
         // sizes that are not a multiple of 32 elements (only possible with blocks of 8 or 16)
         const dim3 grid(grid_for(a.units, kReduceU));
         hipLaunchKernelGGL((dequant_reduce_kernel<E, B, OUT_BF16, kReduceU, kReduceRC, kReduceNTL,
-                                                  false, kHw, OWN>),
+                                                  kReduceNTS, kHw, OWN>),
                            grid, dim3(kThreads), 0, st, a);
     }
     return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_HIP;
-}
-
-template <class E, int B, bool OUT_BF16, bool OWN>
-int launch_reduce_as(const ReduceArgs &a, hipStream_t st)
-{
-    const size_t out_bytes = a.units * 8 * (OUT_BF16 ? 2 : 4);
-    return out_bytes <= kKeepOutputBytes ? launch_reduce_nts<E, B, OUT_BF16, OWN, false>(a, st)
-                                         : launch_reduce_nts<E, B, OUT_BF16, OWN, true>(a, st);
 }
 
 template <class E, int B>
