@@ -51,12 +51,9 @@ constexpr int kReduceRC = 8;        // ranks loaded together, unit form
 // nontemporal stores: measured 5 % faster than plain ones whenever the outputs of successive
 // calls do not all fit the 256 MB last-level cache
 constexpr bool kReduceNTL = true, kReduceNTS = true;
-// ranks loaded together, tile form (measured): 4 where decoding is cheap (one 128-bit load and
-// FP4 conversions, or the whole-chunk BF6 conversion), 2 otherwise
-template <class E> constexpr int tile_rc()
-{
-    return (E::bits == 4 || (E::x == 3 && E::y == 2)) ? 4 : 2;
-}
+// ranks loaded together, tile form (measured: 4 is best or within noise of best for 4-, 5- and
+// 6-bit codes)
+template <class E> constexpr int tile_rc() { return 4; }
 constexpr int kCopyU = 1;
 constexpr bool kHw = true;          // use the scaled-conversion instructions where exact
 

@@ -680,20 +680,21 @@ __device__ __forceinline__ uint32_t stream_bits_rt(const uint32_t (&s)[NW], int 
 // FUSED: instead of storing the sums, quantize them again in the lane that holds them (same
 // rule as the quantizer applied to binary32 input) and store codes and scales; bit-identical to
 // running the unfused kernels one after the other.
+// WG: threads per workgroup (a multiple of 64; each wave works on its own).
 template <class E, int B, bool OUT_BF16, int RC, bool NTL, bool NTS, bool HW, bool FUSED = false,
-          bool OWN = false>
-__global__ __launch_bounds__(kThreads) void dequant_reduce_tile_kernel(ReduceArgs a)
+          bool OWN = false, int WG = kThreads>
+__global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
 {
     constexpr int NB = 32 / B;                   // blocks (scales) per chunk
     constexpr int W = E::bits;                   // dwords of codes per chunk
     constexpr bool kHw = HW && E::hw != HW_NONE;
     constexpr int OC = OUT_BF16 ? 4 : 8;         // 16-byte output pieces per lane
     constexpr bool kChunkBf6 = E::x == 3 && E::y == 2 && B == 32;   // chunk = one hardware BF6 block
-    __shared__ u32x4 tile[kThreads / 64][FUSED ? 1 : 64 * OC];
+    __shared__ u32x4 tile[WG / 64][FUSED ? 1 : 64 * OC];
 
     const int lane = (int)(threadIdx.x & 63);
     const int wave = (int)(threadIdx.x >> 6);
-    const size_t wave_chunk0 = ((size_t)blockIdx.x * (kThreads / 64) + (size_t)wave) * 64;
+    const size_t wave_chunk0 = ((size_t)blockIdx.x * (WG / 64) + (size_t)wave) * 64;
     const size_t chunk = wave_chunk0 + (size_t)lane;
     const size_t nchunks = a.units / 4;
     const bool valid = chunk < nchunks;

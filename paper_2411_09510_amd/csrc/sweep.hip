@@ -166,6 +166,21 @@ static void reduce_tile()
     report(what, ms, N * (n * bits / 8.0 + n / 32.0) + n * 4.0);
 }
 
+template <int X, int Y, int RC, int WG>
+static void reduce_tile_wg()
+{
+    const int bits = 1 + X + Y;
+    const double ms = best_ms([&](int i) {
+        ReduceArgs a = rargs(i, bits);
+        const unsigned g = (unsigned)((units / 4 + WG - 1) / WG);
+        hipLaunchKernelGGL((dequant_reduce_tile_kernel<Elem<X, Y>, 32, false, RC, true, true, true, false, false, WG>),
+                           dim3(g), dim3(WG), 0, 0, a);
+    });
+    char what[96];
+    std::snprintf(what, sizeof what, "reduce tile form e%dm%d  ranks together %d  nt stores 1  workgroup %d", X, Y, RC, WG);
+    report(what, ms, N * (n * bits / 8.0 + n / 32.0) + n * 4.0);
+}
+
 template <int X, int Y, int RC>
 static void fused()
 {
@@ -241,7 +256,12 @@ int main(int argc, char **argv)
     CK(hipDeviceSynchronize());
     std::printf("mxc_sweep: %d partials of [%zu x %zu], block 32, E8M0 scale\n", N, T, H);
 
-    if (std::getenv("MXC_SWEEP_FUSED_FIRST")) { fused<2, 2, 8>(); reduce_tile<2, 2, 2, true>(); }
+    if (std::getenv("MXC_SWEEP_WG")) {
+        reduce_tile_wg<2, 1, 4, 64>(); reduce_tile_wg<2, 1, 4, 128>(); reduce_tile_wg<2, 1, 4, 256>(); reduce_tile_wg<2, 1, 4, 512>();
+        reduce_tile_wg<2, 2, 4, 64>(); reduce_tile_wg<2, 2, 4, 128>(); reduce_tile_wg<2, 2, 4, 256>();
+        reduce_tile_wg<3, 2, 4, 64>(); reduce_tile_wg<3, 2, 4, 128>(); reduce_tile_wg<3, 2, 4, 256>();
+        return 0;
+    }
     copy<1, false>(); copy<4, false>(); copy<4, true>();
     quant<2, 1, 1, false, false>(); quant<2, 1, 2, false, false>(); quant<2, 1, 4, false, false>();
     quant<2, 1, 2, true, false>(); quant<2, 1, 1, true, true>(); quant<2, 1, 2, true, true>();
