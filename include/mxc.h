@@ -17,15 +17,17 @@
  *     row, so hidden % block == 0 is required.
  *   - Element format ExMy: sign-magnitude, b = 1 + ebits + mbits bits, code =
  *     sign << (x+y) | exp << y | mant, exponent bias 2^(x-1)-1, no Inf/NaN codes, exp == 0 is
- *     subnormal.  Scale EsM0: one byte per block holding e + (2^(s-1)-1), the block's values
- *     being code_value * 2^e.  For s = 8 the byte 255 marks a block that held an Inf/NaN.
+ *     subnormal.  Scale EsM0: per block the code e + (2^(s-1)-1), the block's values being
+ *     code_value * 2^e.  For s = 8 the code 255 marks a block that held an Inf/NaN.
  *   - Shared exponent e = floor(log2(max|v|)) - emax clamped to the scale's range; elements are
  *     rounded to the nearest magnitude, ties to the even code, saturating at the largest
  *     magnitude; the sign bit is the input's sign bit.  A block containing Inf/NaN stores
  *     all-zero codes and scale byte 255 (s = 8) or the largest scale code (s < 8).
  *   - Packed codes: element j of a row occupies bits [j*b, (j+1)*b) of the row's little-endian
- *     bit stream, rows back to back (hidden*b/8 bytes each).  Scales: uint8 [tokens x
- *     hidden/block], row-major.
+ *     bit stream, rows back to back (hidden*b/8 bytes each).  Scales, s = 8: uint8 [tokens x
+ *     hidden/block], row-major.  Scales, s < 8: a bit stream over all blocks of the tensor in
+ *     the same order, block k at bits [k*s, (k+1)*s), LSB first, ceil(blocks*s/8) bytes, unused
+ *     bits of the last byte zero.
  *   - Every data pointer is a DEVICE pointer owned by the caller, valid until the stream has
  *     finished the call.  Arrays of pointers (`const void* const*`) are HOST arrays of device
  *     pointers; they are read during the call and need not outlive it.
@@ -52,7 +54,7 @@ typedef struct {
     int32_t ebits;      /* x, 1..3 */
     int32_t mbits;      /* y, 1..4; 3 <= 1+x+y <= 6 */
     int32_t block;      /* 8, 16 or 32 */
-    int32_t scale_bits; /* s, 4..8 (stored one byte per block) */
+    int32_t scale_bits; /* s, 4..8 */
 } mxc_format;
 
 typedef enum {
@@ -77,9 +79,9 @@ const char *mxc_strerror(int status);
 const char *mxc_version(void);
 
 /* Sizes of the packed arrays for one [tokens x hidden] tensor (host only, closed form):
- * code_bytes = tokens*hidden*b/8, scale_bytes = tokens*hidden/block.  Either output pointer may
- * be NULL.  (Model Evaluation: effective bits = b + s/block; with s = 8 the two arrays together
- * are exactly that many bits per element.) */
+ * code_bytes = tokens*hidden*b/8, scale_bytes = ceil(tokens*hidden/block * s / 8).  Either output
+ * pointer may be NULL.  (Model Evaluation: effective bits = b + s/block; the two arrays together
+ * are exactly that many bits per element whenever the scale stream fills its last byte.) */
 int mxc_packed_sizes(const mxc_format *fmt, int64_t tokens, int64_t hidden,
                      size_t *code_bytes, size_t *scale_bytes);
 

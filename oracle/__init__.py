@@ -147,6 +147,27 @@ def unpack(fmt: Format, packed: np.ndarray, hidden: int) -> np.ndarray:
     return out
 
 
+def pack_scales(fmt: Format, scales: np.ndarray) -> np.ndarray:
+    """uint8 scale codes (any shape, one per block, row-major) -> the flat array that travels:
+    the same bytes for s = 8, an s-bit stream for s < 8."""
+    scales = np.ascontiguousarray(scales, dtype=np.uint8)
+    n = scales.size
+    out = np.zeros((n * fmt.scale_bits + 7) // 8, dtype=np.uint8)
+    f = fmt.c()
+    _check(lib().mxo_pack_scales(ctypes.byref(f), _ptr(scales), ctypes.c_int64(n), _ptr(out)),
+           "pack_scales")
+    return out
+
+
+def unpack_scales(fmt: Format, packed: np.ndarray, nblocks: int) -> np.ndarray:
+    packed = np.ascontiguousarray(packed, dtype=np.uint8).ravel()
+    out = np.empty(nblocks, dtype=np.uint8)
+    f = fmt.c()
+    _check(lib().mxo_unpack_scales(ctypes.byref(f), _ptr(packed), ctypes.c_int64(nblocks),
+                                   _ptr(out)), "unpack_scales")
+    return out
+
+
 def dequantize(fmt: Format, codes: np.ndarray, scales: np.ndarray) -> np.ndarray:
     codes = np.ascontiguousarray(codes, dtype=np.uint8)
     scales = np.ascontiguousarray(scales, dtype=np.uint8)

@@ -31,7 +31,9 @@
  *   non-finite   : a block with any Inf/NaN stores all-zero element codes and the marker scale
  *                  (s = 8) or the largest scale code (s < 8).
  *   packing      : element j of a row occupies bits [j*b, (j+1)*b) of the row's little-endian
- *                  bit stream; scales are one byte per block, row-major.
+ *                  bit stream.  Scales: s = 8 one byte per block, row-major; s < 8 a bit stream
+ *                  over all blocks of the tensor, block k at bits [k*s, (k+1)*s), LSB first,
+ *                  the last byte padded with zeros (mxo_pack_scales).
  *   reduction    : out = (((d0 + d1) + d2) + ...), IEEE binary32 adds in rank order, d_r the
  *                  exactly decoded value (a scale byte of 255 decodes the block to NaN).
  *
@@ -95,17 +97,51 @@ int mxo_num_threads(void)
 }
 
 /* Effective bits per element and the sizes of the packed arrays (Model Evaluation; Table 1
- * column 3; Table 3 caption).  code_bytes/scale_bytes describe the layout above; for s < 8 the
- * scale array still spends one byte per block, so effective_bits is the closed form, not the
- * size of these arrays. */
+ * column 3; Table 3 caption).  scale_bytes is ceil(blocks*s/8): whenever blocks*s is a multiple
+ * of 8 the two arrays together are exactly effective_bits per element. */
 int mxo_packed_sizes(const mxo_format *f, int64_t tokens, int64_t hidden,
                      uint64_t *code_bytes, uint64_t *scale_bytes, double *effective_bits)
 {
     if (!fmt_ok(f)) return MXO_ERR_FORMAT;
     if (tokens < 0 || hidden < 0 || hidden % f->block) return MXO_ERR_SHAPE;
+    uint64_t blocks = (uint64_t)tokens * (uint64_t)(hidden / f->block);
     if (code_bytes) *code_bytes = (uint64_t)tokens * (uint64_t)hidden * (uint64_t)fmt_bits(f) / 8u;
-    if (scale_bytes) *scale_bytes = (uint64_t)tokens * (uint64_t)(hidden / f->block);
+    if (scale_bytes) *scale_bytes = (blocks * (uint64_t)f->scale_bits + 7u) / 8u;
     if (effective_bits) *effective_bits = fmt_bits(f) + (double)f->scale_bits / f->block;
+    return MXO_OK;
+}
+
+/* One scale code per byte -> the array that travels: unchanged for s = 8, an s-bit stream for
+ * s < 8 (block k at bits [k*s, (k+1)*s), LSB first, zero padding in the last byte). */
+int mxo_pack_scales(const mxo_format *f, const uint8_t *scale_codes, int64_t nblocks, uint8_t *packed)
+{
+    if (!fmt_ok(f)) return MXO_ERR_FORMAT;
+    if (nblocks < 0) return MXO_ERR_SHAPE;
+    int s = f->scale_bits;
+    if (s == 8) { memcpy(packed, scale_codes, (size_t)nblocks); return MXO_OK; }
+    memset(packed, 0, (size_t)((nblocks * s + 7) / 8));
+    for (int64_t k = 0; k < nblocks; ++k)
+        for (int b = 0; b < s; ++b) {
+            int64_t bit = k * s + b;
+            if ((scale_codes[k] >> b) & 1u) packed[bit >> 3] |= (uint8_t)(1u << (bit & 7));
+        }
+    return MXO_OK;
+}
+
+int mxo_unpack_scales(const mxo_format *f, const uint8_t *packed, int64_t nblocks, uint8_t *scale_codes)
+{
+    if (!fmt_ok(f)) return MXO_ERR_FORMAT;
+    if (nblocks < 0) return MXO_ERR_SHAPE;
+    int s = f->scale_bits;
+    if (s == 8) { memcpy(scale_codes, packed, (size_t)nblocks); return MXO_OK; }
+    for (int64_t k = 0; k < nblocks; ++k) {
+        unsigned c = 0;
+        for (int b = 0; b < s; ++b) {
+            int64_t bit = k * s + b;
+            c |= (unsigned)((packed[bit >> 3] >> (bit & 7)) & 1u) << b;
+        }
+        scale_codes[k] = (uint8_t)c;
+    }
     return MXO_OK;
 }
 

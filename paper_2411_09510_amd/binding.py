@@ -144,9 +144,14 @@ def effective_bits(fmt: Format) -> float:
 
 
 def _alloc_packed(fmt: Format, tokens: int, hidden: int, device):
+    """codes uint8 [tokens, hidden*b/8]; scales uint8 [tokens, hidden/block] for 8-bit scales,
+    a flat bit-stream array for narrower ones."""
     cb, sb = packed_sizes(fmt, tokens, hidden)
     codes = torch.empty((tokens, cb // tokens if tokens else 0), dtype=torch.uint8, device=device)
-    scales = torch.empty((tokens, sb // tokens if tokens else 0), dtype=torch.uint8, device=device)
+    if fmt.scale_bits == 8:
+        scales = torch.empty((tokens, sb // tokens if tokens else 0), dtype=torch.uint8, device=device)
+    else:
+        scales = torch.empty((sb,), dtype=torch.uint8, device=device)
     return codes, scales
 
 

@@ -22,6 +22,7 @@ bool format_ok(const mxc_format *f)
 ScaleFmt scale_fmt(const mxc_format *f)
 {
     ScaleFmt s;
+    s.sbits = f->scale_bits;
     s.sbias = (1 << (f->scale_bits - 1)) - 1;
     s.smax = f->scale_bits == 8 ? 254 : (1 << f->scale_bits) - 1;
     s.nonfinite = f->scale_bits == 8 ? 255 : s.smax;
@@ -280,7 +281,9 @@ int mxc_packed_sizes(const mxc_format *fmt, int64_t tokens, int64_t hidden, size
     if (rc != MXC_OK) return rc;
     const size_t b = (size_t)(1 + fmt->ebits + fmt->mbits);
     if (code_bytes) *code_bytes = units * b;
-    if (scale_bytes) *scale_bytes = units * 8 / (size_t)fmt->block;
+    const size_t blocks = units * 8 / (size_t)fmt->block;
+    if (scale_bytes)
+        *scale_bytes = fmt->scale_bits == 8 ? blocks : (blocks * (size_t)fmt->scale_bits + 7) / 8;
     return MXC_OK;
 }
 

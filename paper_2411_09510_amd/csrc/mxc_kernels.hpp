@@ -53,6 +53,7 @@ struct Elem {
 
 // Scale format EsM0, runtime (s only changes two clamps per block).
 struct ScaleFmt {
+    int sbits;      // s: 8 = one byte per block; 4..7 = packed s-bit stream, LSB first
     int sbias;      // 2^(s-1) - 1
     int smax;       // largest ordinary code: 254 for s = 8, 2^s - 1 otherwise
     int nonfinite;  // code stored for a block that held Inf/NaN: 255 for s = 8, smax otherwise
@@ -158,23 +159,56 @@ __device__ __forceinline__ uint32_t squeeze4(uint32_t bytes)
 // Moving b-bit codes between "8 codes per lane" and the packed little-endian bit stream.
 // A quad of lanes owns 32 codes = b dwords of the stream, at dword index quad*b.
 
-// Store: lane holds its 8 codes in the low 8b bits of v.
+// How many bytes of the quad's b dwords lie inside the array: the last quad of a tensor whose
+// size is not a multiple of 32 elements holds fewer than four units.
+__device__ __forceinline__ int quad_valid_bytes(size_t unit, size_t units_total, int bits)
+{
+    const size_t q0 = unit & ~(size_t)3;
+    const size_t left = units_total > q0 ? units_total - q0 : 0;
+    return (int)(left < 4 ? left : 4) * bits;
+}
+
+// Stores the first `nbytes` bytes of dword v at p (all four when nbytes >= 4, none when <= 0).
+__device__ __forceinline__ void store_prefix(uint32_t *p, uint32_t v, int nbytes)
+{
+    if (nbytes >= 4) {
+        *p = v;
+    } else {
+        for (int k = 0; k < nbytes; ++k) ((uint8_t *)p)[k] = (uint8_t)(v >> (8 * k));
+    }
+}
+
+// Loads the first `nbytes` bytes of the dword at p; the rest reads as zero.
+__device__ __forceinline__ uint32_t load_prefix(const uint32_t *p, int nbytes)
+{
+    if (nbytes >= 4) return *p;
+    uint32_t v = 0;
+    for (int k = 0; k < nbytes; ++k) v |= (uint32_t)((const uint8_t *)p)[k] << (8 * k);
+    return v;
+}
+
+// Store: lane holds its 8 codes in the low 8b bits of v (zero for a unit past the end).  After
+// the in-quad exchange each lane owns up to two whole dwords of the stream (k0, k1; -1 = none).
 template <int BITS, bool NT>
-__device__ __forceinline__ void store_codes(uint32_t *codes, size_t unit, uint64_t v, bool valid)
+__device__ __forceinline__ void store_codes(uint32_t *codes, size_t unit, uint64_t v, size_t units_total)
 {
     const int i = (int)(threadIdx.x & 3);
-    uint32_t *q = codes + (unit >> 2) * BITS;
     if (BITS == 4) {
-        if (valid) st<NT>(codes + unit, (uint32_t)v);
-    } else if (BITS == 5) {
+        if (unit < units_total) st<NT>(codes + unit, (uint32_t)v);
+        return;
+    }
+    int k0 = -1, k1 = -1;
+    uint32_t d0 = 0, d1 = 0;
+    if (BITS == 5) {
         // lane i's 40 bits start at stream bit 40i = dword i, bit 8i
         uint64_t w = v << (8 * i);
         uint32_t lo = (uint32_t)w, hi = (uint32_t)(w >> 32);
         uint32_t from_prev = dpp<quad_perm(3, 0, 1, 2)>(hi);     // lane i gets hi of lane i-1
-        uint32_t d = lo | (i ? from_prev : 0u);
-        if (valid) {
-            st<NT>(q + i, d);
-            if (i == 0) st<NT>(q + 4, from_prev);                // hi of lane 3
+        k0 = i;
+        d0 = lo | (i ? from_prev : 0u);
+        if (i == 0) {                                            // hi of lane 3
+            k1 = 4;
+            d1 = from_prev;
         }
     } else if (BITS == 6) {
         // pairs of lanes own 3 dwords: even lane bits 0..47, odd lane bits 48..95
@@ -182,65 +216,125 @@ __device__ __forceinline__ void store_codes(uint32_t *codes, size_t unit, uint64
         uint32_t lo = (uint32_t)w, hi = (uint32_t)(w >> 32);
         uint32_t give = (i & 1) ? lo : hi;
         uint32_t got = dpp<quad_perm(1, 0, 3, 2)>(give);          // odd lane gets even's hi
-        uint32_t *p = q + 3 * (i >> 1);
-        if (valid) {
-            if (i & 1) {
-                st<NT>(p + 1, lo | got);
-                st<NT>(p + 2, hi);
-            } else {
-                st<NT>(p, lo);
-            }
+        const int p0 = 3 * (i >> 1);                              // first dword of the pair
+        if (i & 1) {
+            k0 = p0 + 1;
+            d0 = lo | got;
+            k1 = p0 + 2;
+            d1 = hi;
+        } else {
+            k0 = p0;
+            d0 = lo;
         }
     } else {  // BITS == 3: lane i's 24 bits start at stream bit 24i
         const int s = (32 - 8 * i) & 31;                          // 0, 24, 16, 8
         uint64_t w = v << s;
         uint32_t lo = (uint32_t)w, hi = (uint32_t)(w >> 32);
         uint32_t from_next = dpp<quad_perm(1, 2, 3, 3)>(lo);      // lane i gets lo of lane i+1
-        uint32_t d = (i ? hi : lo) | from_next;
-        if (valid && i < 3) st<NT>(q + i, d);
+        if (i < 3) {
+            k0 = i;
+            d0 = (i ? hi : lo) | from_next;
+        }
+    }
+    uint32_t *q = codes + (unit >> 2) * BITS;
+    if ((unit | 3) < units_total) {                               // the whole quad is inside
+        if (k0 >= 0) st<NT>(q + k0, d0);
+        if (k1 >= 0) st<NT>(q + k1, d1);
+    } else {                                                      // the tensor's last, partial quad
+        const int vb = quad_valid_bytes(unit, units_total, BITS);
+        if (k0 >= 0) store_prefix(q + k0, d0, vb - 4 * k0);
+        if (k1 >= 0) store_prefix(q + k1, d1, vb - 4 * k1);
     }
 }
 
-// Load: returns the lane's 8 codes in the low 8b bits.
+// Load: returns the lane's 8 codes in the low 8b bits (zero for a unit past the end, or when
+// `on` is false for the whole wave step, e.g. a rank beyond tp).
 template <int BITS, bool NT>
-__device__ __forceinline__ uint64_t load_codes(const uint32_t *codes, size_t unit, bool valid)
+__device__ __forceinline__ uint64_t load_codes(const uint32_t *codes, size_t unit, size_t units_total, bool on)
 {
     const int i = (int)(threadIdx.x & 3);
+    if (BITS == 4) return (on && unit < units_total) ? ld<NT>(codes + unit) : 0u;
+    // the dwords this lane fetches (k0, k1; -1 = none)
+    int k0 = -1, k1 = -1;
+    if (BITS == 5) {
+        k0 = i;
+        k1 = i == 0 ? 4 : -1;
+    } else if (BITS == 6) {
+        const int p0 = 3 * (i >> 1);
+        k0 = (i & 1) ? p0 + 1 : p0;
+        k1 = (i & 1) ? p0 + 2 : -1;
+    } else {
+        k0 = i < 3 ? i : -1;
+    }
     const uint32_t *q = codes + (unit >> 2) * BITS;
-    if (BITS == 4) {
-        return valid ? ld<NT>(codes + unit) : 0u;
-    } else if (BITS == 5) {
-        uint32_t d = 0, extra = 0;
-        if (valid) {
-            d = ld<NT>(q + i);
-            if (i == 0) extra = ld<NT>(q + 4);
-        }
-        uint32_t give = i ? d : extra;
+    uint32_t a = 0, b = 0;
+    if (on && (unit | 3) < units_total) {                         // the whole quad is inside
+        if (k0 >= 0) a = ld<NT>(q + k0);
+        if (k1 >= 0) b = ld<NT>(q + k1);
+    } else if (on) {
+        const int vb = quad_valid_bytes(unit, units_total, BITS);
+        if (k0 >= 0) a = load_prefix(q + k0, vb - 4 * k0);
+        if (k1 >= 0) b = load_prefix(q + k1, vb - 4 * k1);
+    }
+    if (BITS == 5) {
+        uint32_t give = i ? a : b;
         uint32_t next = dpp<quad_perm(1, 2, 3, 0)>(give);         // lane i gets dword i+1
-        uint64_t w = ((uint64_t)next << 32) | d;
+        uint64_t w = ((uint64_t)next << 32) | a;
         return (w >> (8 * i)) & ((1ull << 40) - 1);
     } else if (BITS == 6) {
-        const uint32_t *p = q + 3 * (i >> 1);
-        uint32_t a = 0, b = 0;
-        if (valid) {
-            if (i & 1) {
-                a = ld<NT>(p + 1);
-                b = ld<NT>(p + 2);
-            } else {
-                a = ld<NT>(p);
-            }
-        }
         uint32_t other = dpp<quad_perm(1, 0, 3, 2)>(a);           // even lane gets dword 1
         uint64_t even = (uint64_t)a | ((uint64_t)(other & 0xFFFFu) << 32);
         uint64_t odd = (uint64_t)(a >> 16) | ((uint64_t)b << 16);
         return (i & 1) ? odd : even;
     } else {  // BITS == 3
-        uint32_t d = 0;
-        if (valid && i < 3) d = ld<NT>(q + i);
-        uint32_t prev = dpp<quad_perm(0, 0, 1, 2)>(d);            // lane i gets dword i-1
-        uint64_t w = ((uint64_t)d << 32) | prev;
+        uint32_t prev = dpp<quad_perm(0, 0, 1, 2)>(a);            // lane i gets dword i-1
+        uint64_t w = ((uint64_t)a << 32) | prev;
         return (w >> (32 - 8 * i)) & 0xFFFFFFull;
     }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Narrow scale formats (s < 8) travel as a bit stream: block k's code at bits [k*s, (k+1)*s) of
+// the tensor's scale array, LSB first, the last byte padded with zeros.
+
+// Wave-wide store of 64/G consecutive fields of `width` bits (4..28), field f held by lane f*G in
+// `value` (fields past `nvalid` must hold 0).  `dst` is the byte where field 0 starts, which is
+// always a byte boundary because 64/G fields of any width fill a whole number of bytes.  Lane j
+// assembles byte j (and j+64, ... for wide fields) from the up to three fields that overlap it.
+// Every lane of the wave must call this, and every lane runs the same number of rounds: the
+// cross-lane reads need their source lanes active.
+template <int G>
+__device__ __forceinline__ void store_packed_fields(uint8_t *dst, uint32_t value, int width, int nvalid)
+{
+    constexpr int NF = 64 / G;
+    const int lane = (int)(threadIdx.x & 63);
+    const int nbytes = (nvalid * width + 7) >> 3;
+    const int rounds = (((NF * width) >> 3) + 63) >> 6;
+    for (int t = 0; t < rounds; ++t) {
+        const int j = lane + 64 * t;
+        const int f0 = (8 * j) / width, off = 8 * j - f0 * width;
+        uint32_t bits = 0;
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+            const int f = f0 + k;
+            const uint32_t v = (uint32_t)__builtin_amdgcn_ds_bpermute(4 * min(f, NF - 1) * G, (int)value);
+            const int sh = k * width - off;                   // negative only for k == 0
+            if (f < NF && sh < 8) bits |= sh >= 0 ? v << sh : v >> -sh;
+        }
+        if (j < nbytes) dst[j] = (uint8_t)bits;
+    }
+}
+
+// `nbits` (<= 28) bits starting at bit `bitpos` of a byte array of `total` bytes.
+__device__ __forceinline__ uint32_t load_bits(const uint8_t *base, size_t bitpos, int nbits, size_t total)
+{
+    const size_t byte = bitpos >> 3;
+    const int sh = (int)(bitpos & 7);
+    uint64_t w = 0;
+#pragma unroll
+    for (int k = 0; k < 5; ++k)
+        if (8 * k < sh + nbits && byte + k < total) w |= (uint64_t)base[byte + k] << (8 * k);
+    return (uint32_t)(w >> sh) & ((1u << nbits) - 1u);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -454,10 +548,20 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantArgs a)
         }
         int sc;
         const uint64_t packed = encode_unit<E, SRC32, HW>(w[u], expfield, sf, &sc);
-        store_codes<E::bits, NTS>(codes, unit, packed, valid[u]);
+        store_codes<E::bits, NTS>(codes, unit, packed, a.units);
 
         // Every lane of a block knows the block's scale.
-        if (U % G == 0) {
+        if (sf.sbits < 8) {
+            // packed scale stream: the 64/G scales of this wave step are a byte-aligned run
+            const size_t first_unit = wave_base + (size_t)(u * 64);
+            if (first_unit < a.units) {
+                const size_t first_block = first_unit / G;
+                const size_t left = a.units / G - first_block;
+                store_packed_fields<G>(scales + ((first_block * (size_t)sf.sbits) >> 3),
+                                       valid[u] ? (uint32_t)sc : 0u, sf.sbits,
+                                       (int)(left < (size_t)(64 / G) ? left : (size_t)(64 / G)));
+            }
+        } else if (U % G == 0) {
             // Over G consecutive steps lane l keeps the scale of step (l % G); after the G-th
             // step each lane stores one byte, so the wave writes 64 consecutive scale bytes.
             if ((lane & (G - 1)) == (u & (G - 1))) my_scale = sc;
@@ -607,8 +711,15 @@ __global__ __launch_bounds__(kThreads) void dequant_reduce_kernel(ReduceArgs a)
             for (int i = 0; i < RC; ++i) {
                 const bool on = valid && (r0 + i < a.tp) && !(OWN && r0 + i == a.own_rank);
                 const int r = min(r0 + i, a.tp - 1);
-                v[i] = load_codes<E::bits, NTL>((const uint32_t *)a.codes[r], unit, on);
-                sc[i] = on ? (int)ld<NTL>((const uint8_t *)a.scales[r] + unit / G) : sf.sbias;
+                v[i] = load_codes<E::bits, NTL>((const uint32_t *)a.codes[r], unit, a.units,
+                                                r0 + i < a.tp && !(OWN && r0 + i == a.own_rank));
+                if (!on)
+                    sc[i] = sf.sbias;
+                else if (sf.sbits == 8)
+                    sc[i] = (int)ld<NTL>((const uint8_t *)a.scales[r] + unit / G);
+                else
+                    sc[i] = (int)load_bits((const uint8_t *)a.scales[r], (unit / G) * (size_t)sf.sbits,
+                                           sf.sbits, (a.units / G * (size_t)sf.sbits + 7) >> 3);
             }
 #pragma unroll
             for (int i = 0; i < RC; ++i) {
@@ -736,11 +847,19 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
             }
             // NB scale bytes, little-endian in one register; idle lanes read as "e = 0"
             uint32_t sb = (uint32_t)sf.sbias * 0x01010101u;
-            if (on) {
+            if (on && sf.sbits == 8) {
                 const uint8_t *sp = (const uint8_t *)a.scales[r] + chunk * NB;
                 if (NB == 1) sb = ld<NTL>(sp);
                 else if (NB == 2) sb = ld<NTL>((const uint16_t *)sp);
                 else sb = ld<NTL>((const uint32_t *)sp);
+            } else if (on) {
+                // packed stream: NB fields of s bits, re-spread to one byte each
+                const uint32_t raw = load_bits((const uint8_t *)a.scales[r], chunk * NB * (size_t)sf.sbits,
+                                               NB * sf.sbits, (nchunks * NB * (size_t)sf.sbits + 7) >> 3);
+                sb = 0;
+#pragma unroll
+                for (int n = 0; n < NB; ++n)
+                    sb |= ((raw >> (n * sf.sbits)) & ((1u << sf.sbits) - 1u)) << (8 * n);
             }
             sw[i] = sb;
         }
@@ -890,10 +1009,21 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
 #pragma unroll
                 for (int k = 0; k < W; ++k) st<NTS>(cp + k, cw[k]);
             }
-            uint8_t *sp = (uint8_t *)a.scales_out + chunk * NB;
-            if (NB == 1) *sp = (uint8_t)sbytes;
-            else if (NB == 2) *(uint16_t *)sp = (uint16_t)sbytes;
-            else *(uint32_t *)sp = sbytes;
+            if (sf.sbits == 8) {
+                uint8_t *sp = (uint8_t *)a.scales_out + chunk * NB;
+                if (NB == 1) *sp = (uint8_t)sbytes;
+                else if (NB == 2) *(uint16_t *)sp = (uint16_t)sbytes;
+                else *(uint32_t *)sp = sbytes;
+            }
+        }
+        if (sf.sbits < 8 && wave_chunk0 < nchunks) {
+            // packed scale stream: each lane contributes NB fields of s bits = one wider field
+            uint32_t field = 0;
+#pragma unroll
+            for (int n = 0; n < NB; ++n) field |= ((sbytes >> (8 * n)) & 0xFFu) << (n * sf.sbits);
+            const size_t left = nchunks - wave_chunk0;
+            store_packed_fields<1>((uint8_t *)a.scales_out + ((wave_chunk0 * NB * (size_t)sf.sbits) >> 3),
+                                   valid ? field : 0u, NB * sf.sbits, (int)(left < 64 ? left : 64));
         }
         return;
     }

@@ -69,7 +69,7 @@ struct Buffers {
     void *out[3];         // binary32 tensors (reduce output / requantize input)
 };
 static Buffers b;
-static const ScaleFmt sf{127, 254, 255, 1};
+static const ScaleFmt sf{8, 127, 254, 255, 1};
 
 static QuantArgs qargs(int i, int bits)
 {

@@ -35,6 +35,8 @@ def test_packed_sizes_and_effective_bits(L):
     assert mxc.packed_sizes(mxc.Format(2, 2, 32, 8), 4096, 8192) == (20 << 20, 1 << 20)
     assert mxc.packed_sizes(mxc.Format(3, 2, 16, 8), 4096, 8192) == (24 << 20, 2 << 20)
     assert mxc.packed_sizes(mxc.Format(2, 1, 32, 8), 0, 8192) == (0, 0)
+    assert mxc.packed_sizes(mxc.Format(2, 1, 8, 5), 64, 4096) == (64 * 4096 // 2, 64 * 512 * 5 // 8)
+    assert mxc.packed_sizes(mxc.Format(2, 1, 8, 5), 1, 24) == (12, 2)    # 3 blocks, 15 bits -> 2 bytes
     assert mxc.effective_bits(mxc.Format(2, 1, 32, 8)) == 4.25          # Table 3 caption
     assert mxc.effective_bits(mxc.Format(2, 1, 8, 5)) == 4.625          # Table 1 prints 4.6
     with pytest.raises(mxc.MxcError):

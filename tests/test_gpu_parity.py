@@ -30,6 +30,25 @@ def host(t):
     return t.cpu().numpy()
 
 
+def dev_scales(oracle_mod, fo, codes):
+    """Scale codes [T, H/B] -> the device array the library reads (bit stream for s < 8)."""
+    if fo.scale_bits == 8:
+        return torch.from_numpy(np.ascontiguousarray(codes)).cuda()
+    return torch.from_numpy(oracle_mod.pack_scales(fo, codes)).cuda()
+
+
+def host_scales(oracle_mod, fo, t, shape):
+    """Device scale array as written by the library -> scale codes of the given shape; for
+    s < 8 also checks that the stream is exactly the oracle's packing of those codes."""
+    raw = host(t)
+    if fo.scale_bits == 8:
+        return raw.reshape(shape)
+    n = int(np.prod(shape))
+    codes = oracle_mod.unpack_scales(fo, raw, n)
+    assert np.array_equal(raw.ravel(), oracle_mod.pack_scales(fo, codes)), "padding bits not zero"
+    return codes.reshape(shape)
+
+
 def same_f32(a, b):
     a, b = np.asarray(a, np.float32), np.asarray(b, np.float32)
     nan_a, nan_b = np.isnan(a), np.isnan(b)
@@ -43,7 +62,7 @@ def check_quantize(mxc, oracle_mod, x, y, B, bits, s=8):
     codes, scales = mxc.quantize(fg, dev_bf16(bits))
     torch.cuda.synchronize()
     ocodes, oscales = oracle_mod.quantize_bf16(fo, bits)
-    assert np.array_equal(host(scales), oscales), "scales differ"
+    assert np.array_equal(host_scales(oracle_mod, fo, scales, oscales.shape), oscales), "scales differ"
     got = oracle_mod.unpack(fo, host(codes), bits.shape[1])
     if not np.array_equal(got, ocodes):
         bad = np.argwhere(got != ocodes)[0]
@@ -74,21 +93,39 @@ def test_quantize_ragged_shapes(mxc, oracle_mod, T, H):
             check_quantize(mxc, oracle_mod, x, y, B, bits)
 
 
-def test_quantize_does_not_write_past_the_end(mxc, oracle_mod):
-    for (x, y) in HOT + [(1, 1)]:
-        fg = mxc.Format(x, y, 32, 8)
-        T, H = 3, 96
-        cb, sb = mxc.packed_sizes(fg, T, H)
-        codes = torch.full((cb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
-        scales = torch.full((sb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
-        w = workloads.Workload("canary", 1, T, H, seed=3)
-        xin = dev_bf16(workloads.partial_bf16(w, 0))
-        mxc.quantize(fg, xin, codes[:cb].view(T, -1), scales[:sb].view(T, -1))
-        torch.cuda.synchronize()
-        assert (codes[cb:] == 0xA5).all() and (scales[sb:] == 0xA5).all()
-        ocodes, oscales = oracle_mod.quantize_bf16(oracle_mod.Format(x, y, 32, 8),
-                                                   workloads.partial_bf16(w, 0))
-        assert np.array_equal(host(scales[:sb]).reshape(T, -1), oscales)
+@pytest.mark.parametrize("x,y", [(2, 1), (2, 2), (3, 2), (1, 1), (3, 1), (1, 4)])
+def test_quantize_sizes_that_are_not_multiples_of_32(mxc, oracle_mod, x, y):
+    """Blocks of 8 or 16 allow tensors whose size is not a multiple of 32 elements: the last
+    quad of lanes then holds 1 to 3 units and the packed stream ends inside a dword.  Outputs
+    must be exact and nothing may be written past them (canaries), for every code width and
+    for 8-bit and narrow scales."""
+    for (B, T, H) in ((8, 1, 8), (8, 1, 40), (8, 3, 24), (8, 5, 1048), (8, 7, 2056), (16, 1, 16),
+                      (16, 3, 48), (16, 5, 1040), (32, 3, 96)):
+        for s in (8, 5):
+            fo, fg = oracle_mod.Format(x, y, B, s), mxc.Format(x, y, B, s)
+            cb, sb = mxc.packed_sizes(fg, T, H)
+            codes = torch.full((cb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+            scales = torch.full((sb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+            w = workloads.Workload("canary", 1, T, H, seed=3 + T + H)
+            bits = workloads.partial_bf16(w, 0)
+            mxc.quantize(fg, dev_bf16(bits), codes[:cb], scales[:sb])
+            # the same through the binary32 front end (requantize of the exact values)
+            codes32 = torch.full((cb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+            scales32 = torch.full((sb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+            xf = torch.from_numpy(workloads.bf16_bits_to_f32(bits)).cuda()
+            mxc.requantize_chunk(fg, xf, 1, 0, codes32[:cb], scales32[:sb])
+            torch.cuda.synchronize()
+            ocodes, oscales = oracle_mod.quantize_bf16(fo, bits)
+            for c_, s_ in ((codes, scales), (codes32, scales32)):
+                assert (c_[cb:] == 0xA5).all() and (s_[sb:] == 0xA5).all(), (B, T, H, s)
+                assert np.array_equal(host_scales(oracle_mod, fo, s_[:sb], oscales.shape), oscales)
+                assert np.array_equal(host(c_[:cb]).reshape(T, -1), oracle_mod.pack(fo, ocodes)), (B, T, H, s)
+            # and back: the reduce of this one partial is its exact decode
+            out = torch.full((T * H + 64,), 7.0, dtype=torch.float32, device="cuda")
+            mxc.dequant_reduce(fg, [codes[:cb]], [scales[:sb]], T, H, out=out[:T * H].view(T, H))
+            torch.cuda.synchronize()
+            assert (out[T * H:] == 7.0).all()
+            assert same_f32(host(out[:T * H]).reshape(T, H), oracle_mod.dequantize(fo, ocodes, oscales))
 
 
 @pytest.mark.parametrize("x,y", ALL_ELEMENTS)
@@ -180,7 +217,7 @@ def oracle_partials(oracle_mod, fo, w):
 
 def check_reduce(mxc, oracle_mod, fo, fg, cs, ss, T, H):
     packed = [torch.from_numpy(oracle_mod.pack(fo, c)).cuda() for c in cs]
-    scales = [torch.from_numpy(s).cuda() for s in ss]
+    scales = [dev_scales(oracle_mod, fo, s) for s in ss]
     out = mxc.dequant_reduce(fg, packed, scales, T, H)
     out16 = mxc.dequant_reduce(fg, packed, scales, T, H, out_dtype=torch.bfloat16)
     torch.cuda.synchronize()
@@ -382,33 +419,48 @@ def test_fused_reduce_requantize_equals_unfused_pair(mxc, oracle_mod, x, y, B):
         assert np.array_equal(host(cf), oracle_mod.pack(fo, oc))
 
 
-@pytest.mark.parametrize("s", [4, 5, 7])
+@pytest.mark.parametrize("s", [4, 5, 6, 7])
 def test_fused_and_requantize_with_narrow_scales(mxc, oracle_mod, s):
-    """Narrow scale formats clamp at both ends: sums far above the range saturate, far below
-    round to zero, in the fused form and in requantize alike."""
+    """Narrow scale formats clamp at both ends (sums far above the range saturate, far below
+    round to zero) and travel as an s-bit stream, in the fused form and in requantize alike;
+    shapes with whole wave tiles, with a ragged tail, and one that takes the unit-form reduce."""
     rng = np.random.default_rng(s)
-    T, H, tp = 8, 1024, 4
-    for (x, y, B) in ((3, 2, 32), (2, 1, 32), (2, 2, 16)):
+    for (x, y, B, T, H, tp) in ((3, 2, 32, 8, 1024, 4), (2, 1, 32, 3, 2080, 3), (2, 2, 16, 5, 1040, 2),
+                                (2, 1, 8, 9, 1032, 2), (1, 1, 8, 1, 40, 3)):
         fo, fg = oracle_mod.Format(x, y, B, s), mxc.Format(x, y, B, s)
         top = 2 ** s - 1
         ocs = [rng.integers(0, 2 ** fo.bits, size=(T, H), dtype=np.uint8) for _ in range(tp)]
         oss = [rng.integers(0, top + 1, size=(T, H // B), dtype=np.uint8) for _ in range(tp)]
         packed = [torch.from_numpy(oracle_mod.pack(fo, c)).cuda() for c in ocs]
-        scales = [torch.from_numpy(v).cuda() for v in oss]
+        scales = [dev_scales(oracle_mod, fo, v) for v in oss]
+        cb, sb = mxc.packed_sizes(fg, T, H)
+        assert scales[0].numel() == sb == (T * (H // B) * s + 7) // 8
         red = mxc.dequant_reduce(fg, packed, scales, T, H)
         # stretch the reduced tensor far outside the scale range for the requantize check
         wide = red.clone()
-        wide[1] *= 2.0 ** 60
-        wide[2] *= 2.0 ** -60
-        c2, s2 = mxc.requantize_chunk(fg, wide, 1, 0)
-        cf, sf_ = mxc.dequant_reduce_requantize(fg, packed, scales, T, H)
+        wide[0] *= 2.0 ** 60
+        if T > 2:
+            wide[2] *= 2.0 ** -60
+        sbuf = torch.full((sb + 16,), 0xA5, dtype=torch.uint8, device="cuda")
+        c2, s2 = mxc.requantize_chunk(fg, wide, 1, 0, scales=sbuf[:sb],
+                                      codes=torch.empty((T, cb // T), dtype=torch.uint8, device="cuda"))
         torch.cuda.synchronize()
+        assert (sbuf[sb:] == 0xA5).all()
         want = oracle_mod.dequant_reduce(fo, ocs, oss)
         assert same_f32(host(red), want)
-        oc, os_ = oracle_mod.quantize_f32(fo, want)
-        assert np.array_equal(host(sf_), os_) and np.array_equal(host(cf), oracle_mod.pack(fo, oc))
         oc, os_ = oracle_mod.quantize_f32(fo, host(wide))
-        assert np.array_equal(host(s2), os_) and np.array_equal(host(c2), oracle_mod.pack(fo, oc))
+        assert np.array_equal(host_scales(oracle_mod, fo, s2, os_.shape), os_)
+        assert np.array_equal(host(c2), oracle_mod.pack(fo, oc))
+        if (T * H) % 32 == 0:
+            fbuf = torch.full((sb + 16,), 0xA5, dtype=torch.uint8, device="cuda")
+            cf, sf_ = mxc.dequant_reduce_requantize(
+                fg, packed, scales, T, H, torch.empty((T, cb // T), dtype=torch.uint8, device="cuda"),
+                fbuf[:sb])
+            torch.cuda.synchronize()
+            assert (fbuf[sb:] == 0xA5).all()
+            oc, os_ = oracle_mod.quantize_f32(fo, want)
+            assert np.array_equal(host_scales(oracle_mod, fo, sf_, os_.shape), os_)
+            assert np.array_equal(host(cf), oracle_mod.pack(fo, oc))
 
 
 def test_requantize_f32_rounding_corners(mxc, oracle_mod):

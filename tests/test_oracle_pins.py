@@ -163,6 +163,27 @@ def test_compression_ratio_closed_form(oracle_mod):
     assert round(lo, 1) == 3.5 and round(hi, 1) == 4.4
 
 
+def test_scale_stream_and_wire_size_for_every_scale_format(oracle_mod):
+    """Narrow scales travel as an s-bit stream, so the arrays' real sizes give the closed-form
+    effective bits for every scale format (Table 1 was printed with 5-bit scales)."""
+    rng = np.random.default_rng(8)
+    for s in (4, 5, 6, 7, 8):
+        fmt = oracle_mod.Format(2, 1, 8, s)
+        T, H = 16, 1024
+        cb, sb, eff = oracle_mod.packed_sizes(fmt, T, H)
+        assert sb == T * (H // 8) * s // 8
+        assert abs((cb + sb) * 8 / (T * H) - eff) < 1e-12 and eff == 4 + s / 8
+        top = 255 if s == 8 else 2 ** s
+        codes = rng.integers(0, top, size=(5, 13), dtype=np.uint8)          # 65 blocks: ragged tail
+        packed = oracle_mod.pack_scales(fmt, codes)
+        stream = sum(int(c) << (k * s) for k, c in enumerate(codes.ravel()))
+        assert bytes(packed) == stream.to_bytes((65 * s + 7) // 8, "little")
+        assert np.array_equal(oracle_mod.unpack_scales(fmt, packed, 65), codes.ravel())
+    # FP4, block 8, 5-bit scale: 4.625 bits -> the paper's 3.5x
+    cb, sb, eff = oracle_mod.packed_sizes(oracle_mod.Format(2, 1, 8, 5), 64, 4096)
+    assert round(64 * 4096 * 2 / (cb + sb), 1) == 3.5
+
+
 def test_packed_sizes_are_array_sizes(oracle_mod):
     for (x, y) in ALL_ELEMENTS:
         for B in (8, 16, 32):
