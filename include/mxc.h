@@ -33,7 +33,8 @@
  *     pointers; they are read during the call and need not outlive it.
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Each call
  *     validates its arguments on the host, enqueues its kernel(s) on that stream and returns
- *     without synchronising.  The library allocates nothing and keeps no state.
+ *     without synchronising.  The library allocates nothing and keeps no state (other than the
+ *     pair of events mxc_time_next_launch arms for one launch of the calling thread).
  *   - Return value: MXC_OK or a negative mxc_status.  On error nothing has been enqueued.
  *   - Alignment: bf16/f32 tensors and packed code arrays must be 16-byte aligned, scale arrays
  *     4-byte aligned (MXC_ERR_ALIGN otherwise).  A requantize chunk's rows start at multiples of
@@ -145,6 +146,16 @@ int mxc_dequant_reduce_requantize(const mxc_format *fmt, int tp, const void *con
  * dst on the device with 128-bit loads and stores.  Its rate is the practical ceiling the
  * codec kernels are compared with. */
 int mxc_copy_probe(void *dst, const void *src, size_t bytes, void *hip_stream);
+
+/* Measurement aid: arm a pair of HIP events (hipEvent_t passed as void*, created by the caller with
+ * timing enabled; either may be NULL) for the calling thread.  The next kernel this thread
+ * launches through any entry point above stamps start_event when the kernel begins and
+ * stop_event when it ends, from the dispatch's own timestamps, so hipEventElapsedTime between
+ * them is the kernel's duration without the launch gap, and no extra packet enters the stream.
+ * The pair is used once and then forgotten; a call that fails validation launches nothing and
+ * leaves it armed; (NULL, NULL) disarms.  Do not arm events for launches under stream capture.
+ * Always returns MXC_OK. */
+int mxc_time_next_launch(void *start_event, void *stop_event);
 
 #ifdef __cplusplus
 }

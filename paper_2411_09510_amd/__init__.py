@@ -7,11 +7,11 @@ from .binding import (Format, Launch, MxcError, copy_probe, dequant_reduce,
                       prepare_dequant_reduce_requantize,
                       packed_sizes, prepare_dequant_reduce, prepare_quantize_batched,
                       prepare_requantize_chunk, quantize, quantize_batched, requantize_chunk,
-                      version)
+                      time_next_launch, version)
 
 __all__ = ["Format", "Launch", "MxcError", "copy_probe", "dequant_reduce",
            "dequant_reduce_own", "dequant_reduce_requantize", "prepare_dequant_reduce_requantize",
            "int_format", "effective_bits", "lib",
            "packed_sizes", "prepare_dequant_reduce", "prepare_quantize_batched",
            "prepare_requantize_chunk", "quantize", "quantize_batched", "requantize_chunk",
-           "version"]
+           "time_next_launch", "version"]

@@ -95,6 +95,8 @@ def lib() -> ctypes.CDLL:
                                                     i64, i64, vp, vp, vp]
         L.mxc_copy_probe.restype = ci
         L.mxc_copy_probe.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        L.mxc_time_next_launch.restype = ci
+        L.mxc_time_next_launch.argtypes = [vp, vp]
         _lib = L
     return _lib
 
@@ -340,3 +342,19 @@ def copy_probe(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
     nbytes = src.numel() * src.element_size()
     _check(lib().mxc_copy_probe(dst.data_ptr(), src.data_ptr(), nbytes, _stream(stream)),
            "mxc_copy_probe")
+
+
+def _event_handle(ev) -> ctypes.c_void_p:
+    if ev is None:
+        return ctypes.c_void_p(None)
+    if not ev.cuda_event:
+        ev.record()             # torch creates the HIP event on its first record
+    return ctypes.c_void_p(ev.cuda_event)
+
+
+def time_next_launch(start, stop) -> None:
+    """Arm two ``torch.cuda.Event(enable_timing=True)`` (or None) for the next kernel this thread
+    launches through the library: ``start.elapsed_time(stop)`` is then that kernel's own duration
+    (mxc_time_next_launch).  Synchronise before reading the events."""
+    _check(lib().mxc_time_next_launch(_event_handle(start), _event_handle(stop)),
+           "mxc_time_next_launch")

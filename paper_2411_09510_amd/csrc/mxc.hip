@@ -4,6 +4,8 @@
 
 #include "mxc_kernels.hpp"
 
+#include <hip/hip_ext.h>
+
 namespace {
 
 using namespace mxc;
@@ -64,13 +66,30 @@ unsigned grid_for(size_t units, int per_lane)
     return (unsigned)((units + per_group - 1) / per_group);
 }
 
+// Events armed by mxc_time_next_launch for the calling thread; the next launch consumes them.
+thread_local hipEvent_t t_start = nullptr, t_stop = nullptr;
+
+// Every kernel of the library is enqueued here.  With armed events the launch goes through the
+// extended launch call, which stamps them from the dispatch's own begin and end timestamps and
+// adds no packet to the stream.
+template <class... Args>
+int launch(void (*kernel)(Args...), dim3 grid, hipStream_t st, Args... args)
+{
+    if (t_start || t_stop) {
+        hipExtLaunchKernelGGL(kernel, grid, dim3(kThreads), 0, st, t_start, t_stop, 0, args...);
+        t_start = t_stop = nullptr;
+    } else {
+        hipLaunchKernelGGL(kernel, grid, dim3(kThreads), 0, st, args...);
+    }
+    return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_HIP;
+}
+
 template <class E, int B, bool SRC32>
 int launch_quantize(const QuantArgs &a, int n, hipStream_t st)
 {
     constexpr int U = SRC32 ? kQuantU32 : kQuantU;
-    hipLaunchKernelGGL((quantize_kernel<E, B, SRC32, U, kQuantNTL, kQuantNTS, kHw, SRC32>),
-                       dim3(grid_for(a.units, U), (unsigned)n), dim3(kThreads), 0, st, a);
-    return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_HIP;
+    return launch(quantize_kernel<E, B, SRC32, U, kQuantNTL, kQuantNTS, kHw, SRC32>,
+                  dim3(grid_for(a.units, U), (unsigned)n), st, a);
 }
 
 template <class E, bool SRC32>
@@ -107,17 +126,16 @@ int launch_reduce_as(const ReduceArgs &a, hipStream_t st)
         // whole 32-element chunks: one lane per chunk, output staged through LDS
         const size_t chunks = a.units / 4;
         const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads));
-        hipLaunchKernelGGL((dequant_reduce_tile_kernel<E, B, OUT_BF16, tile_rc<E>(), kReduceNTL,
-                                                       kReduceNTS, kHw, false, OWN>),
-                           grid, dim3(kThreads), 0, st, a);
+        return launch(dequant_reduce_tile_kernel<E, B, OUT_BF16, tile_rc<E>(), kReduceNTL,
+                                                 kReduceNTS, kHw, false, OWN>,
+                      grid, st, a);
     } else {
         // sizes that are not a multiple of 32 elements (only possible with blocks of 8 or 16)
         const dim3 grid(grid_for(a.units, kReduceU));
-        hipLaunchKernelGGL((dequant_reduce_kernel<E, B, OUT_BF16, kReduceU, kReduceRC, kReduceNTL,
-                                                  kReduceNTS, kHw, OWN>),
-                           grid, dim3(kThreads), 0, st, a);
+        return launch(dequant_reduce_kernel<E, B, OUT_BF16, kReduceU, kReduceRC, kReduceNTL,
+                                            kReduceNTS, kHw, OWN>,
+                      grid, st, a);
     }
-    return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_HIP;
 }
 
 template <class E, int B>
@@ -136,9 +154,8 @@ int launch_fused(const ReduceArgs &a, hipStream_t st)
     const size_t chunks = a.units / 4;
     const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads));
     // no LDS tile and a read-dominated stream: all eight ranks' loads in flight at once
-    hipLaunchKernelGGL((dequant_reduce_tile_kernel<E, B, false, 8, kReduceNTL, kQuantNTS, kHw, true>),
-                       grid, dim3(kThreads), 0, st, a);
-    return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_HIP;
+    return launch(dequant_reduce_tile_kernel<E, B, false, 8, kReduceNTL, kQuantNTS, kHw, true>, grid,
+                  st, a);
 }
 
 template <class E>
@@ -387,9 +404,15 @@ int mxc_copy_probe(void *dst, const void *src, size_t bytes, void *hip_stream)
     if (!aligned(dst, 16) || !aligned(src, 16)) return MXC_ERR_ALIGN;
     if (bytes == 0) return MXC_OK;
     const size_t n16 = bytes / 16;
-    hipLaunchKernelGGL((copy_kernel<kCopyU, false>), dim3(grid_for(n16, kCopyU)), dim3(kThreads),
-                       0, (hipStream_t)hip_stream, (u32x4 *)dst, (const u32x4 *)src, n16);
-    return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_HIP;
+    return launch(copy_kernel<kCopyU, false>, dim3(grid_for(n16, kCopyU)), (hipStream_t)hip_stream,
+                  (u32x4 *)dst, (const u32x4 *)src, n16);
+}
+
+int mxc_time_next_launch(void *start_event, void *stop_event)
+{
+    t_start = (hipEvent_t)start_event;
+    t_stop = (hipEvent_t)stop_event;
+    return MXC_OK;
 }
 
 }  // extern "C"

@@ -19,6 +19,7 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace mxc {
 
@@ -169,19 +170,21 @@ __device__ __forceinline__ int quad_valid_bytes(size_t unit, size_t units_total,
 }
 
 // Stores the first `nbytes` bytes of dword v at p (all four when nbytes >= 4, none when <= 0).
+template <bool NT>
 __device__ __forceinline__ void store_prefix(uint32_t *p, uint32_t v, int nbytes)
 {
     if (nbytes >= 4) {
-        *p = v;
+        st<NT>(p, v);           // same kind of store as the full-quad path, so merging the two keeps it
     } else {
         for (int k = 0; k < nbytes; ++k) ((uint8_t *)p)[k] = (uint8_t)(v >> (8 * k));
     }
 }
 
 // Loads the first `nbytes` bytes of the dword at p; the rest reads as zero.
+template <bool NT>
 __device__ __forceinline__ uint32_t load_prefix(const uint32_t *p, int nbytes)
 {
-    if (nbytes >= 4) return *p;
+    if (nbytes >= 4) return ld<NT>(p);
     uint32_t v = 0;
     for (int k = 0; k < nbytes; ++k) v |= (uint32_t)((const uint8_t *)p)[k] << (8 * k);
     return v;
@@ -242,14 +245,15 @@ __device__ __forceinline__ void store_codes(uint32_t *codes, size_t unit, uint64
         if (k1 >= 0) st<NT>(q + k1, d1);
     } else {                                                      // the tensor's last, partial quad
         const int vb = quad_valid_bytes(unit, units_total, BITS);
-        if (k0 >= 0) store_prefix(q + k0, d0, vb - 4 * k0);
-        if (k1 >= 0) store_prefix(q + k1, d1, vb - 4 * k1);
+        if (k0 >= 0) store_prefix<NT>(q + k0, d0, vb - 4 * k0);
+        if (k1 >= 0) store_prefix<NT>(q + k1, d1, vb - 4 * k1);
     }
 }
 
 // Load: returns the lane's 8 codes in the low 8b bits (zero for a unit past the end, or when
-// `on` is false for the whole wave step, e.g. a rank beyond tp).
-template <int BITS, bool NT>
+// `on` is false for the whole wave step, e.g. a rank beyond tp).  TAIL = false promises that no
+// lane of the wave step sits in the tensor's last, partial quad, and leaves that path out.
+template <int BITS, bool NT, bool TAIL = true>
 __device__ __forceinline__ uint64_t load_codes(const uint32_t *codes, size_t unit, size_t units_total, bool on)
 {
     const int i = (int)(threadIdx.x & 3);
@@ -271,10 +275,10 @@ __device__ __forceinline__ uint64_t load_codes(const uint32_t *codes, size_t uni
     if (on && (unit | 3) < units_total) {                         // the whole quad is inside
         if (k0 >= 0) a = ld<NT>(q + k0);
         if (k1 >= 0) b = ld<NT>(q + k1);
-    } else if (on) {
+    } else if (TAIL && on) {
         const int vb = quad_valid_bytes(unit, units_total, BITS);
-        if (k0 >= 0) a = load_prefix(q + k0, vb - 4 * k0);
-        if (k1 >= 0) b = load_prefix(q + k1, vb - 4 * k1);
+        if (k0 >= 0) a = load_prefix<NT>(q + k0, vb - 4 * k0);
+        if (k1 >= 0) b = load_prefix<NT>(q + k1, vb - 4 * k1);
     }
     if (BITS == 5) {
         uint32_t give = i ? a : b;
@@ -696,8 +700,10 @@ __global__ __launch_bounds__(kThreads) void dequant_reduce_kernel(ReduceArgs a)
         ((size_t)blockIdx.x * (kThreads / 64) + (size_t)wave) * (size_t)(U * 64);
     const ScaleFmt sf = a.sf;
 
-#pragma unroll 1
-    for (int u = 0; u < U; ++u) {
+    // One wave step; `tail` (a std::bool_constant) says whether the step may touch the tensor's
+    // last, partial quad of units.  Only the last step of the last wave does, and keeping that
+    // case out of the common step keeps its loads free of branches, so they issue together.
+    auto step = [&](int u, auto tail) {
         const size_t unit = wave_base + (size_t)(u * 64 + lane);
         const bool valid = unit < a.units;
         float acc[8];
@@ -711,8 +717,9 @@ __global__ __launch_bounds__(kThreads) void dequant_reduce_kernel(ReduceArgs a)
             for (int i = 0; i < RC; ++i) {
                 const bool on = valid && (r0 + i < a.tp) && !(OWN && r0 + i == a.own_rank);
                 const int r = min(r0 + i, a.tp - 1);
-                v[i] = load_codes<E::bits, NTL>((const uint32_t *)a.codes[r], unit, a.units,
-                                                r0 + i < a.tp && !(OWN && r0 + i == a.own_rank));
+                v[i] = load_codes<E::bits, NTL, decltype(tail)::value>(
+                    (const uint32_t *)a.codes[r], unit, a.units,
+                    r0 + i < a.tp && !(OWN && r0 + i == a.own_rank));
                 if (!on)
                     sc[i] = sf.sbias;
                 else if (sf.sbits == 8)
@@ -764,6 +771,14 @@ __global__ __launch_bounds__(kThreads) void dequant_reduce_kernel(ReduceArgs a)
                 st<NTS>(o + 1, f32x4{acc[4], acc[5], acc[6], acc[7]});
             }
         }
+    };
+#pragma unroll 1
+    for (int u = 0; u < U; ++u) {
+        const size_t last_unit = wave_base + (size_t)(u * 64 + 63);
+        if ((a.units & 3) != 0 && last_unit >= (a.units & ~(size_t)3))
+            step(u, std::true_type{});
+        else
+            step(u, std::false_type{});
     }
 }
 

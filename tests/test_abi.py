@@ -24,7 +24,8 @@ def declared_functions():
 def test_header_functions_are_exported(L):
     names = declared_functions()
     assert {"mxc_quantize", "mxc_quantize_batched", "mxc_dequant_reduce", "mxc_requantize_chunk",
-            "mxc_dequant_reduce_requantize", "mxc_dequant_reduce_own", "mxc_packed_sizes", "mxc_strerror", "mxc_copy_probe"} <= set(names)
+            "mxc_dequant_reduce_requantize", "mxc_dequant_reduce_own", "mxc_packed_sizes", "mxc_strerror", "mxc_copy_probe",
+            "mxc_time_next_launch"} <= set(names)
     for n in names:
         assert getattr(L, n) is not None, n
 
@@ -101,6 +102,7 @@ def test_host_side_argument_errors(L):
     assert L.mxc_copy_probe(good, good, 24, None) == -3
     assert L.mxc_copy_probe(good, odd, 32, None) == -4
     assert L.mxc_copy_probe(good, good, 0, None) == 0
+    assert L.mxc_time_next_launch(None, None) == 0          # disarming needs no device
     for code in range(-8, 1):
         assert L.mxc_strerror(code)
     assert b"gfx950" in L.mxc_version()

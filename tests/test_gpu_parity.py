@@ -525,6 +525,37 @@ def test_calls_run_on_the_stream_they_are_given(mxc, oracle_mod):
             assert np.array_equal(host(scales[r]), oss[r])
 
 
+def test_timed_launch_gives_the_same_result_and_a_kernel_duration(mxc, oracle_mod):
+    """Events armed for one launch are stamped by that launch only, leave its output unchanged,
+    and measure a duration inside the host-side wall time of the synchronised call."""
+    import time
+    fo, fg = oracle_mod.Format(2, 2, 32, 8), mxc.Format(2, 2, 32, 8)
+    w = workloads.Workload("timed", 4, 256, 4096, seed=77, n_outlier=4, outlier_mult=(20.0, 100.0))
+    parts = [workloads.partial_bf16(w, r) for r in range(w.tp)]
+    xs = [dev_bf16(p) for p in parts]
+    codes, scales = mxc.quantize_batched(fg, xs)            # also warms the kernels up
+    out = torch.empty((w.tokens, w.hidden), dtype=torch.float32, device="cuda")
+    mxc.dequant_reduce(fg, codes, scales, w.tokens, w.hidden, out=out)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    mxc.time_next_launch(ev[0], ev[1])
+    codes, scales = mxc.quantize_batched(fg, xs)
+    mxc.time_next_launch(ev[2], ev[3])
+    mxc.dequant_reduce(fg, codes, scales, w.tokens, w.hidden, out=out)
+    mxc.dequant_reduce(fg, codes, scales, w.tokens, w.hidden, out=out)   # not timed: pair was used
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    q_ms, r_ms = ev[0].elapsed_time(ev[1]), ev[2].elapsed_time(ev[3])
+    assert 0.0 < q_ms < wall_ms and 0.0 < r_ms < wall_ms
+    assert ev[1].elapsed_time(ev[2]) >= 0.0                # the reduce began after the quantize ended
+    ocs, oss = zip(*[oracle_mod.quantize_bf16(fo, p) for p in parts])
+    for r in range(w.tp):
+        assert np.array_equal(host(codes[r]).reshape(w.tokens, -1), oracle_mod.pack(fo, ocs[r]))
+        assert np.array_equal(host(scales[r]), oss[r])
+    assert same_f32(host(out), oracle_mod.dequant_reduce(fo, list(ocs), list(oss)))
+
+
 # ------------------------------------------------------------------------ HIP graphs --------
 
 def test_calls_can_be_captured_in_a_hip_graph(mxc, oracle_mod):
