@@ -695,3 +695,45 @@ def test_full_size_other_configs_sampled_rows(mxc, oracle_mod, cfg):
         cb, sb = mxc.packed_sizes(fg, w.tokens, w.hidden)
         assert abs(w.tokens * w.hidden * 2 / (cb + sb) - 16 / (fo.bits + s / B)) < 1e-9
         del codes, scales, out
+
+
+@pytest.mark.parametrize("x,y", [(2, 1), (2, 2)])
+def test_tensor_beyond_two_to_the_32_elements(mxc, oracle_mod, x, y):
+    """One tensor of 2^32 + 2^17 elements (32769 rows of 131072), so element indices, byte offsets
+    of the bf16 input, of the packed codes and of the float32 output all cross 2^31 and 2^32
+    inside the tensor.  Rows on both sides of every such boundary, the first and the last row
+    are checked element by element against the oracle; the scale rule is checked everywhere."""
+    T, H, B = 32769, 131072, 32
+    fo, fg = oracle_mod.Format(x, y, B, 8), mxc.Format(x, y, B, 8)
+    gen = torch.Generator(device="cuda").manual_seed(4100 + x * 10 + y)
+    xd = torch.empty((T, H), dtype=torch.bfloat16, device="cuda")
+    for a in range(0, T, 4096):
+        b = min(T, a + 4096)
+        blk = torch.randn((b - a, H), generator=gen, device="cuda")
+        blk *= torch.exp2(torch.randint(-12, 6, (b - a, 1), generator=gen, device="cuda").float())
+        xd[a:b] = blk.bfloat16()
+        del blk
+    rows = np.array([0, 1, 8191, 8192, 16383, 16384, 16385, 24577, 32767, 32768])
+    codes, scales = mxc.quantize(fg, xd)
+    out = mxc.dequant_reduce(fg, [codes, codes], [scales, scales], T, H)
+    out16 = mxc.dequant_reduce(fg, [codes, codes], [scales, scales], T, H, out_dtype=torch.bfloat16)
+    cf, sf_ = mxc.dequant_reduce_requantize(fg, [codes, codes], [scales, scales], T, H)
+    torch.cuda.synchronize()
+    xr = host(xd[rows].view(torch.int16)).view(np.uint16)
+    oc, os_ = oracle_mod.quantize_bf16(fo, xr)
+    assert np.array_equal(host(scales[rows]), os_)
+    assert np.array_equal(host(codes[rows]), oracle_mod.pack(fo, oc))
+    want = oracle_mod.dequant_reduce(fo, [oc, oc], [os_, os_])
+    assert same_f32(host(out[rows]), want)
+    assert np.array_equal(host(out16[rows].view(torch.int16)).view(np.uint16),
+                          oracle_mod.round_to_bf16(want))
+    oc2, os2 = oracle_mod.quantize_f32(fo, want)
+    assert np.array_equal(host(sf_[rows]), os2)
+    assert np.array_equal(host(cf[rows]), oracle_mod.pack(fo, oc2))
+    # scale rule on every block of the tensor
+    emax = 2 ** x - 1 - (2 ** (x - 1) - 1)
+    for a in range(0, T, 8192):
+        b = min(T, a + 8192)
+        expf = (xd[a:b].view(torch.int16) >> 7) & 0xFF
+        blockmax = expf.view(b - a, -1, B).max(dim=2).values.to(torch.int32)
+        assert torch.equal(scales[a:b].to(torch.int32), (blockmax - emax).clamp_(min=0))
