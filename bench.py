@@ -192,23 +192,26 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    q_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events.values()]))
-    r_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in events.values()]))
+    q_all = [e[0].elapsed_time(e[1]) for e in events.values()]
+    r_all = [e[2].elapsed_time(e[3]) for e in events.values()]
+    q_ms, r_ms = float(np.mean(q_all)), float(np.mean(r_all))
 
     bf16_bytes = N * T * H * 2
     q_bytes, r_bytes = algorithmic_bytes(fmt, N, T, H)
     value = bf16_bytes / (ms_per_step * 1e-3) / 1e9
     fname = f"e{x}m{y}"
 
-    def roof(kernel, nbytes, ms):
+    def roof(kernel, nbytes, samples):
+        ms = float(np.mean(samples))
         ach = nbytes / (ms * 1e-3) / 1e9
         return {"kernel": kernel, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
                 "traffic": read_traffic(w.name, kernel, fname),
                 "algorithmic_bytes_per_launch": nbytes, "avg_launch_ms": ms,
-                "launches_timed": len(events)}
+                "median_launch_ms": float(np.median(samples)),
+                "min_launch_ms": float(np.min(samples)), "launches_timed": len(samples)}
 
-    rq, rr = roof("quantize_kernel", q_bytes, q_ms), roof("dequant_reduce_kernel", r_bytes, r_ms)
+    rq, rr = roof("quantize_kernel", q_bytes, q_all), roof("dequant_reduce_kernel", r_bytes, r_all)
     dominant = rq if q_ms >= r_ms else rr
 
     result = {
@@ -249,6 +252,8 @@ def main():
         copy_gbs = 2 * (512 << 20) / (cms * 1e-3) / 1e9
         result["copy_ceiling"] = {"GBps": copy_gbs, "frac_of_peak": copy_gbs / HBM_PEAK_GBS,
                                   "bytes_moved": 2 * (512 << 20)}
+        for k in result["kernels"].values():
+            k["frac_of_copy_ceiling"] = k["achieved"] / copy_gbs
         del src, dst
         sweep = {}
         for (fx, fy, fb, fs) in w.formats:

@@ -1,17 +1,22 @@
 """Builds ``libmxc.so`` (HIP kernels + C ABI) for gfx950 with hipcc, in-tree."""
 from __future__ import annotations
 
+import glob
 import os
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SRC = os.path.join(HERE, "csrc", "mxc.hip")
-DEPS = [SRC, os.path.join(HERE, "csrc", "mxc_kernels.hpp"), os.path.join(ROOT, "include", "mxc.h")]
+CSRC = os.path.join(HERE, "csrc")
+# mxc.hip holds the C ABI; every mxc_*.hip instantiates one family of kernels
+SRCS = [os.path.join(CSRC, "mxc.hip")] + sorted(glob.glob(os.path.join(CSRC, "mxc_*.hip")))
+DEPS = SRCS + sorted(glob.glob(os.path.join(CSRC, "*.hpp"))) + [os.path.join(ROOT, "include", "mxc.h")]
+OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmxc.so")
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # the oracle's arithmetic has no fused multiply-adds; the kernels say so where they want one
     "-ffp-contract=off",
     # never let the compiler form packed-fp32 instructions
@@ -26,10 +31,22 @@ def build(force: bool = True) -> str:
             all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in DEPS):
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-o", LIB + ".tmp", SRC]
-    proc = subprocess.run(cmd, capture_output=True, text=True)
-    if proc.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + proc.stdout + proc.stderr)
+    os.makedirs(OBJ_DIR, exist_ok=True)
+
+    def run(cmd):
+        proc = subprocess.run(cmd, capture_output=True, text=True)
+        if proc.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + proc.stdout + proc.stderr)
+
+    def compile_one(src):
+        obj = os.path.join(OBJ_DIR, os.path.splitext(os.path.basename(src))[0] + ".o")
+        run([hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-c", src, "-o", obj])
+        return obj
+
+    # the translation units are independent: compile them side by side, then link
+    with ThreadPoolExecutor(max_workers=min(len(SRCS), os.cpu_count() or 1, 16)) as pool:
+        objs = list(pool.map(compile_one, SRCS))
+    run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB + ".tmp", *objs])
     os.replace(LIB + ".tmp", LIB)
     return LIB
 
@@ -41,7 +58,7 @@ SWEEP_BIN = os.path.join(HERE, "mxc_sweep")
 def build_sweep() -> str:
     """Compile the variant-timing tool ``mxc_sweep`` (optional; the library does not need it)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    flags = [f for f in HIPCC_FLAGS if f not in ("-fPIC", "-shared")]
+    flags = [f for f in HIPCC_FLAGS if f != "-fPIC"]
     cmd = [hipcc, *flags, "-I", os.path.join(ROOT, "include"), "-o", SWEEP_BIN, SWEEP_SRC]
     proc = subprocess.run(cmd, capture_output=True, text=True)
     if proc.returncode != 0:

@@ -1,14 +1,19 @@
 // Host side of the mxc C ABI: argument validation and kernel dispatch.  See include/mxc.h for
 // the contract of every entry point.
-#include "mxc.h"
+#include "mxc_dispatch.hpp"
 
-#include "mxc_kernels.hpp"
+namespace mxc {
+namespace host {
 
-#include <hip/hip_ext.h>
+thread_local hipEvent_t t_start = nullptr, t_stop = nullptr;
+
+}  // namespace host
+}  // namespace mxc
 
 namespace {
 
 using namespace mxc;
+using namespace mxc::host;
 
 bool format_ok(const mxc_format *f)
 {
@@ -44,172 +49,6 @@ int shape_units(const mxc_format *f, int64_t tokens, int64_t hidden, size_t *uni
 
 bool aligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
-// Launch shapes, chosen by measurement on MI355X (HBM-bound kernels: more, smaller waves and
-// nontemporal loads stream best).
-constexpr int kQuantU = 2;          // units per lane, quantize from bf16
-constexpr int kQuantU32 = 1;        // units per lane, quantize from binary32 (LDS-transposed loads)
-constexpr bool kQuantNTL = true, kQuantNTS = true;
-constexpr int kReduceU = 4;         // units per lane, dequant-reduce
-constexpr int kReduceRC = 8;        // ranks loaded together, unit form
-// nontemporal stores: measured 5 % faster than plain ones whenever the outputs of successive
-// calls do not all fit the 256 MB last-level cache
-constexpr bool kReduceNTL = true, kReduceNTS = true;
-// ranks loaded together, tile form (measured: 4 is best or within noise of best for 4-, 5- and
-// 6-bit codes)
-template <class E> constexpr int tile_rc() { return 4; }
-constexpr int kCopyU = 1;
-constexpr bool kHw = true;          // use the scaled-conversion instructions where exact
-
-unsigned grid_for(size_t units, int per_lane)
-{
-    const size_t per_group = (size_t)kThreads * (size_t)per_lane;
-    return (unsigned)((units + per_group - 1) / per_group);
-}
-
-// Events armed by mxc_time_next_launch for the calling thread; the next launch consumes them.
-thread_local hipEvent_t t_start = nullptr, t_stop = nullptr;
-
-// Every kernel of the library is enqueued here.  With armed events the launch goes through the
-// extended launch call, which stamps them from the dispatch's own begin and end timestamps and
-// adds no packet to the stream.
-template <class... Args>
-int launch(void (*kernel)(Args...), dim3 grid, hipStream_t st, Args... args)
-{
-    if (t_start || t_stop) {
-        hipExtLaunchKernelGGL(kernel, grid, dim3(kThreads), 0, st, t_start, t_stop, 0, args...);
-        t_start = t_stop = nullptr;
-    } else {
-        hipLaunchKernelGGL(kernel, grid, dim3(kThreads), 0, st, args...);
-    }
-    return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_HIP;
-}
-
-template <class E, int B, bool SRC32>
-int launch_quantize(const QuantArgs &a, int n, hipStream_t st)
-{
-    constexpr int U = SRC32 ? kQuantU32 : kQuantU;
-    return launch(quantize_kernel<E, B, SRC32, U, kQuantNTL, kQuantNTS, kHw, SRC32>,
-                  dim3(grid_for(a.units, U), (unsigned)n), st, a);
-}
-
-template <class E, bool SRC32>
-int quantize_by_block(int block, const QuantArgs &a, int n, hipStream_t st)
-{
-    switch (block) {
-    case 8: return launch_quantize<E, 8, SRC32>(a, n, st);
-    case 16: return launch_quantize<E, 16, SRC32>(a, n, st);
-    default: return launch_quantize<E, 32, SRC32>(a, n, st);
-    }
-}
-
-template <bool SRC32>
-int quantize_by_format(const mxc_format *f, const QuantArgs &a, int n, hipStream_t st)
-{
-    switch (f->ebits * 10 + f->mbits) {
-    case 11: return quantize_by_block<Elem<1, 1>, SRC32>(f->block, a, n, st);
-    case 12: return quantize_by_block<Elem<1, 2>, SRC32>(f->block, a, n, st);
-    case 13: return quantize_by_block<Elem<1, 3>, SRC32>(f->block, a, n, st);
-    case 14: return quantize_by_block<Elem<1, 4>, SRC32>(f->block, a, n, st);
-    case 21: return quantize_by_block<Elem<2, 1>, SRC32>(f->block, a, n, st);
-    case 22: return quantize_by_block<Elem<2, 2>, SRC32>(f->block, a, n, st);
-    case 23: return quantize_by_block<Elem<2, 3>, SRC32>(f->block, a, n, st);
-    case 31: return quantize_by_block<Elem<3, 1>, SRC32>(f->block, a, n, st);
-    case 32: return quantize_by_block<Elem<3, 2>, SRC32>(f->block, a, n, st);
-    default: return MXC_ERR_FORMAT;
-    }
-}
-
-template <class E, int B, bool OUT_BF16, bool OWN>
-int launch_reduce_as(const ReduceArgs &a, hipStream_t st)
-{
-    if (a.units % 4 == 0) {
-        // whole 32-element chunks: one lane per chunk, output staged through LDS
-        const size_t chunks = a.units / 4;
-        const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads));
-        return launch(dequant_reduce_tile_kernel<E, B, OUT_BF16, tile_rc<E>(), kReduceNTL,
-                                                 kReduceNTS, kHw, false, OWN>,
-                      grid, st, a);
-    } else {
-        // sizes that are not a multiple of 32 elements (only possible with blocks of 8 or 16)
-        const dim3 grid(grid_for(a.units, kReduceU));
-        return launch(dequant_reduce_kernel<E, B, OUT_BF16, kReduceU, kReduceRC, kReduceNTL,
-                                            kReduceNTS, kHw, OWN>,
-                      grid, st, a);
-    }
-}
-
-template <class E, int B>
-int launch_reduce(const ReduceArgs &a, bool out_bf16, hipStream_t st)
-{
-    const bool own = a.own_rank >= 0;
-    if (out_bf16) return own ? launch_reduce_as<E, B, true, true>(a, st)
-                             : launch_reduce_as<E, B, true, false>(a, st);
-    return own ? launch_reduce_as<E, B, false, true>(a, st)
-               : launch_reduce_as<E, B, false, false>(a, st);
-}
-
-template <class E, int B>
-int launch_fused(const ReduceArgs &a, hipStream_t st)
-{
-    const size_t chunks = a.units / 4;
-    const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads));
-    // no LDS tile and a read-dominated stream: all eight ranks' loads in flight at once
-    return launch(dequant_reduce_tile_kernel<E, B, false, 8, kReduceNTL, kQuantNTS, kHw, true>, grid,
-                  st, a);
-}
-
-template <class E>
-int fused_by_block(int block, const ReduceArgs &a, hipStream_t st)
-{
-    switch (block) {
-    case 8: return launch_fused<E, 8>(a, st);
-    case 16: return launch_fused<E, 16>(a, st);
-    default: return launch_fused<E, 32>(a, st);
-    }
-}
-
-int fused_by_format(const mxc_format *f, const ReduceArgs &a, hipStream_t st)
-{
-    switch (f->ebits * 10 + f->mbits) {
-    case 11: return fused_by_block<Elem<1, 1>>(f->block, a, st);
-    case 12: return fused_by_block<Elem<1, 2>>(f->block, a, st);
-    case 13: return fused_by_block<Elem<1, 3>>(f->block, a, st);
-    case 14: return fused_by_block<Elem<1, 4>>(f->block, a, st);
-    case 21: return fused_by_block<Elem<2, 1>>(f->block, a, st);
-    case 22: return fused_by_block<Elem<2, 2>>(f->block, a, st);
-    case 23: return fused_by_block<Elem<2, 3>>(f->block, a, st);
-    case 31: return fused_by_block<Elem<3, 1>>(f->block, a, st);
-    case 32: return fused_by_block<Elem<3, 2>>(f->block, a, st);
-    default: return MXC_ERR_FORMAT;
-    }
-}
-
-template <class E>
-int reduce_by_block(int block, const ReduceArgs &a, bool out_bf16, hipStream_t st)
-{
-    switch (block) {
-    case 8: return launch_reduce<E, 8>(a, out_bf16, st);
-    case 16: return launch_reduce<E, 16>(a, out_bf16, st);
-    default: return launch_reduce<E, 32>(a, out_bf16, st);
-    }
-}
-
-int reduce_by_format(const mxc_format *f, const ReduceArgs &a, bool out_bf16, hipStream_t st)
-{
-    switch (f->ebits * 10 + f->mbits) {
-    case 11: return reduce_by_block<Elem<1, 1>>(f->block, a, out_bf16, st);
-    case 12: return reduce_by_block<Elem<1, 2>>(f->block, a, out_bf16, st);
-    case 13: return reduce_by_block<Elem<1, 3>>(f->block, a, out_bf16, st);
-    case 14: return reduce_by_block<Elem<1, 4>>(f->block, a, out_bf16, st);
-    case 21: return reduce_by_block<Elem<2, 1>>(f->block, a, out_bf16, st);
-    case 22: return reduce_by_block<Elem<2, 2>>(f->block, a, out_bf16, st);
-    case 23: return reduce_by_block<Elem<2, 3>>(f->block, a, out_bf16, st);
-    case 31: return reduce_by_block<Elem<3, 1>>(f->block, a, out_bf16, st);
-    case 32: return reduce_by_block<Elem<3, 2>>(f->block, a, out_bf16, st);
-    default: return MXC_ERR_FORMAT;
-    }
-}
-
 int quantize_common(const mxc_format *fmt, int n, const void *const *x, bool src32,
                     int64_t tokens, int64_t hidden, void *const *codes, void *const *scales,
                     void *hip_stream)
@@ -234,8 +73,7 @@ int quantize_common(const mxc_format *fmt, int n, const void *const *x, bool src
     }
     a.sf = scale_fmt(fmt);
     hipStream_t st = (hipStream_t)hip_stream;
-    return src32 ? quantize_by_format<true>(fmt, a, n, st)
-                 : quantize_by_format<false>(fmt, a, n, st);
+    return src32 ? quantize_f32(fmt, a, n, st) : quantize_bf16(fmt, a, n, st);
 }
 
 // Validation shared by the reduce entry points; fills the pointer tables of `a`.
@@ -339,7 +177,8 @@ int mxc_dequant_reduce(const mxc_format *fmt, int tp, const void *const *codes,
     if (!aligned(out, 16)) return MXC_ERR_ALIGN;
     if (a.units == 0) return MXC_OK;
     a.out = out;
-    return reduce_by_format(fmt, a, out_dtype == MXC_BF16, (hipStream_t)hip_stream);
+    return out_dtype == MXC_BF16 ? reduce_to_bf16(fmt, a, (hipStream_t)hip_stream)
+                                 : reduce_to_f32(fmt, a, (hipStream_t)hip_stream);
 }
 
 int mxc_dequant_reduce_own(const mxc_format *fmt, int tp, int own_rank, const void *own_x_bf16,
@@ -356,7 +195,8 @@ int mxc_dequant_reduce_own(const mxc_format *fmt, int tp, int own_rank, const vo
     if (!aligned(out, 16) || !aligned(own_x_bf16, 16)) return MXC_ERR_ALIGN;
     if (a.units == 0) return MXC_OK;
     a.out = out;
-    return reduce_by_format(fmt, a, out_dtype == MXC_BF16, (hipStream_t)hip_stream);
+    return out_dtype == MXC_BF16 ? reduce_own_to_bf16(fmt, a, (hipStream_t)hip_stream)
+                                 : reduce_own_to_f32(fmt, a, (hipStream_t)hip_stream);
 }
 
 int mxc_dequant_reduce_requantize(const mxc_format *fmt, int tp, const void *const *codes,
@@ -372,7 +212,7 @@ int mxc_dequant_reduce_requantize(const mxc_format *fmt, int tp, const void *con
     if (a.units == 0) return MXC_OK;
     a.codes_out = codes_out;
     a.scales_out = scales_out;
-    return fused_by_format(fmt, a, (hipStream_t)hip_stream);
+    return reduce_requantize(fmt, a, (hipStream_t)hip_stream);
 }
 
 int mxc_requantize_chunk(const mxc_format *fmt, const void *reduced, int in_dtype, int64_t tokens,

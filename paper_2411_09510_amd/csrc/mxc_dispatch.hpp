@@ -1,0 +1,132 @@
+// Host-side plumbing shared by the library's translation units: launch shapes, the one function
+// through which every kernel is enqueued, and the format dispatch.  The kernels of each family
+// (quantize from bf16, quantize from binary32, the four reduce variants, the fused form) are
+// instantiated in a translation unit of their own so that they compile side by side.
+#pragma once
+
+#include "mxc.h"
+
+#include "mxc_kernels.hpp"
+
+#include <hip/hip_ext.h>
+
+#include <type_traits>
+
+namespace mxc {
+namespace host {
+
+// Launch shapes, chosen by measurement on MI355X (HBM-bound kernels: more, smaller waves and
+// nontemporal loads stream best).
+constexpr int kQuantU = 2;          // units per lane, quantize from bf16
+constexpr int kQuantU32 = 1;        // units per lane, quantize from binary32 (LDS-transposed loads)
+constexpr bool kQuantNTL = true, kQuantNTS = true;
+constexpr int kReduceU = 4;         // units per lane, dequant-reduce
+constexpr int kReduceRC = 8;        // ranks loaded together, unit form
+// nontemporal stores: measured 5 % faster than plain ones whenever the outputs of successive
+// calls do not all fit the 256 MB last-level cache
+constexpr bool kReduceNTL = true, kReduceNTS = true;
+// ranks loaded together, tile form (measured: 4 is best or within noise of best for 4-, 5- and
+// 6-bit codes)
+constexpr int kTileRC = 4;
+constexpr int kFusedRC = 8;         // no LDS tile and a read-dominated stream: all ranks in flight
+constexpr int kCopyU = 1;
+constexpr bool kHw = true;          // use the scaled-conversion instructions where exact
+
+inline unsigned grid_for(size_t units, int per_lane)
+{
+    const size_t per_group = (size_t)kThreads * (size_t)per_lane;
+    return (unsigned)((units + per_group - 1) / per_group);
+}
+
+// Events armed by mxc_time_next_launch for the calling thread; the next launch consumes them.
+extern thread_local hipEvent_t t_start, t_stop;
+
+// Every kernel of the library is enqueued here.  With armed events the launch goes through the
+// extended launch call, which stamps them from the dispatch's own begin and end timestamps and
+// adds no packet to the stream.
+template <class... Args>
+int launch(void (*kernel)(Args...), dim3 grid, hipStream_t st, Args... args)
+{
+    if (t_start || t_stop) {
+        hipExtLaunchKernelGGL(kernel, grid, dim3(kThreads), 0, st, t_start, t_stop, 0, args...);
+        t_start = t_stop = nullptr;
+    } else {
+        hipLaunchKernelGGL(kernel, grid, dim3(kThreads), 0, st, args...);
+    }
+    return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_HIP;
+}
+
+// Calls fn(Elem<x, y>{}, std::integral_constant<int, block>{}) for the format's element type and
+// block size (both validated by the caller).
+template <class Fn>
+int for_block(int block, Fn fn)
+{
+    switch (block) {
+    case 8: return fn(std::integral_constant<int, 8>{});
+    case 16: return fn(std::integral_constant<int, 16>{});
+    default: return fn(std::integral_constant<int, 32>{});
+    }
+}
+
+template <class Fn>
+int for_format(const mxc_format *f, Fn fn)
+{
+    auto with = [&](auto elem) { return for_block(f->block, [&](auto block) { return fn(elem, block); }); };
+    switch (f->ebits * 10 + f->mbits) {
+    case 11: return with(Elem<1, 1>{});
+    case 12: return with(Elem<1, 2>{});
+    case 13: return with(Elem<1, 3>{});
+    case 14: return with(Elem<1, 4>{});
+    case 21: return with(Elem<2, 1>{});
+    case 22: return with(Elem<2, 2>{});
+    case 23: return with(Elem<2, 3>{});
+    case 31: return with(Elem<3, 1>{});
+    case 32: return with(Elem<3, 2>{});
+    default: return MXC_ERR_FORMAT;
+    }
+}
+
+// One per translation unit of kernels.  All take validated arguments and enqueue one kernel.
+int quantize_bf16(const mxc_format *f, const QuantArgs &a, int n, hipStream_t st);
+int quantize_f32(const mxc_format *f, const QuantArgs &a, int n, hipStream_t st);
+int reduce_to_f32(const mxc_format *f, const ReduceArgs &a, hipStream_t st);
+int reduce_to_bf16(const mxc_format *f, const ReduceArgs &a, hipStream_t st);
+int reduce_own_to_f32(const mxc_format *f, const ReduceArgs &a, hipStream_t st);
+int reduce_own_to_bf16(const mxc_format *f, const ReduceArgs &a, hipStream_t st);
+int reduce_requantize(const mxc_format *f, const ReduceArgs &a, hipStream_t st);
+
+template <bool SRC32>
+int quantize_any(const mxc_format *f, const QuantArgs &a, int n, hipStream_t st)
+{
+    return for_format(f, [&](auto elem, auto block) {
+        using E = decltype(elem);
+        constexpr int B = decltype(block)::value;
+        constexpr int U = SRC32 ? kQuantU32 : kQuantU;
+        return launch(quantize_kernel<E, B, SRC32, U, kQuantNTL, kQuantNTS, kHw, SRC32>,
+                      dim3(grid_for(a.units, U), (unsigned)n), st, a);
+    });
+}
+
+template <bool OUT_BF16, bool OWN>
+int reduce_any(const mxc_format *f, const ReduceArgs &a, hipStream_t st)
+{
+    return for_format(f, [&](auto elem, auto block) {
+        using E = decltype(elem);
+        constexpr int B = decltype(block)::value;
+        if (a.units % 4 == 0) {
+            // whole 32-element chunks: one lane per chunk, output staged through LDS
+            const size_t chunks = a.units / 4;
+            const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads));
+            return launch(dequant_reduce_tile_kernel<E, B, OUT_BF16, kTileRC, kReduceNTL,
+                                                     kReduceNTS, kHw, false, OWN>,
+                          grid, st, a);
+        }
+        // sizes that are not a multiple of 32 elements (only possible with blocks of 8 or 16)
+        return launch(dequant_reduce_kernel<E, B, OUT_BF16, kReduceU, kReduceRC, kReduceNTL,
+                                            kReduceNTS, kHw, OWN>,
+                      dim3(grid_for(a.units, kReduceU)), st, a);
+    });
+}
+
+}  // namespace host
+}  // namespace mxc

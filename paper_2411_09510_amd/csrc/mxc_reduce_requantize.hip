@@ -1,0 +1,20 @@
+// Kernels behind mxc::host::reduce_requantize: the fused dequant-reduce + requantize form.
+#include "mxc_dispatch.hpp"
+
+namespace mxc {
+namespace host {
+
+int reduce_requantize(const mxc_format *f, const ReduceArgs &a, hipStream_t st)
+{
+    return for_format(f, [&](auto elem, auto block) {
+        using E = decltype(elem);
+        constexpr int B = decltype(block)::value;
+        const size_t chunks = a.units / 4;
+        const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads));
+        return launch(dequant_reduce_tile_kernel<E, B, false, kFusedRC, kReduceNTL, kQuantNTS, kHw, true>,
+                      grid, st, a);
+    });
+}
+
+}  // namespace host
+}  // namespace mxc
