@@ -47,6 +47,9 @@ def parse_args():
                     help="seconds of untimed load before the warm-up steps (clock conditioning)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the untimed format sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--quality-table", action="store_true",
+                    help="add the quality proxy (SQNR of the reduced output) for every element "
+                         "format, block size and scale width to the JSON line")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows per partial for the oracle timing")
     return ap.parse_args()
 
@@ -103,6 +106,33 @@ def cpu_baseline(w, x, y, host_parts, rows):
         "quantize_GBps": nbytes / (t1 - t0) / 1e9, "dequant_reduce_GBps": nbytes / (t2 - t1) / 1e9,
         "seconds": t2 - t0,
     }
+
+
+def quality_table(mxc, torch, xs, T, H):
+    """Quality proxy over the paper's whole parameter list (Method: element type, block size,
+    scale type): SQNR in dB of the compressed TP reduction against the uncompressed sum of the
+    same synthetic partials.  It stands in for the perplexity tables (Model Evaluation and the
+    appendix ablation), which need models and data.  The error is computed with plain torch
+    outside the library."""
+    exact = xs[0].float()
+    for t in xs[1:]:
+        exact += t.float()
+    power = float(exact.double().pow(2).sum())
+    out = torch.empty((T, H), dtype=torch.float32, device="cuda")
+    table = {}
+    elements = [(1, 1), (1, 2), (2, 1), (1, 3), (2, 2), (3, 1), (1, 4), (2, 3), (3, 2)]
+    for (fx, fy) in elements:
+        for fb in (8, 16, 32):
+            for fs in (8, 7, 6, 5, 4):
+                f = mxc.Format(fx, fy, fb, fs)
+                codes, scales = mxc.quantize_batched(f, xs)
+                mxc.dequant_reduce(f, codes, scales, T, H, out=out)
+                err = float((out - exact).double().pow(2).sum())
+                table[f"e{fx}m{fy}_b{fb}_s{fs}"] = {
+                    "effective_bits": mxc.effective_bits(f),
+                    "sqnr_db": 10.0 * float(np.log10(power / err)) if err > 0 else float("inf")}
+                del codes, scales
+    return table
 
 
 def main():
@@ -360,6 +390,9 @@ def main():
             "step_quantize_%d_plus_reduce_graph_replay_us" % N: graph_us,
         }
         result["sweep"] = sweep
+
+    if args.quality_table:
+        result["quality_table"] = quality_table(mxc, torch, x_sets[0], T, H)
 
     if not args.no_cpu_baseline:
         rows = args.cpu_rows or min(T, 4096)

@@ -174,7 +174,9 @@ template <bool NT>
 __device__ __forceinline__ void store_prefix(uint32_t *p, uint32_t v, int nbytes)
 {
     if (nbytes >= 4) {
-        st<NT>(p, v);           // same kind of store as the full-quad path, so merging the two keeps it
+        // the same kind of store as the full-quad path: the compiler merges the two, and a merge
+        // of a nontemporal store with a plain one would come out plain
+        st<NT>(p, v);
     } else {
         for (int k = 0; k < nbytes; ++k) ((uint8_t *)p)[k] = (uint8_t)(v >> (8 * k));
     }
