@@ -737,3 +737,53 @@ def test_tensor_beyond_two_to_the_32_elements(mxc, oracle_mod, x, y):
         expf = (xd[a:b].view(torch.int16) >> 7) & 0xFF
         blockmax = expf.view(b - a, -1, B).max(dim=2).values.to(torch.int32)
         assert torch.equal(scales[a:b].to(torch.int32), (blockmax - emax).clamp_(min=0))
+
+
+# ------------------------------------------------------------------------ random cases ------
+
+def random_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for k in range(count):
+        x, y = ALL_ELEMENTS[rng.integers(len(ALL_ELEMENTS))]
+        B = int(rng.choice([8, 16, 32]))
+        s = int(rng.choice([8, 8, 8, 7, 6, 5, 4]))
+        tp = int(rng.integers(1, 10))
+        T = int(rng.integers(1, 40))
+        H = B * int(rng.integers(1, 70))
+        cases.append((k, x, y, B, s, tp, T, H))
+    return cases
+
+
+@pytest.mark.parametrize("k,x,y,B,s,tp,T,H", random_cases(96, 20241109))
+def test_random_configurations(mxc, oracle_mod, k, x, y, B, s, tp, T, H):
+    """Formats, scale widths, tp, shapes (ragged, not multiples of 32 elements included) and
+    stress inputs drawn from a seeded generator; every entry point against the oracle."""
+    fo, fg = oracle_mod.Format(x, y, B, s), mxc.Format(x, y, B, s)
+    parts = [workloads.stress_bf16(9000 + 100 * k + r, T, H) for r in range(tp)]
+    if k % 3 == 0:      # activations-like values instead, so that sums are not dominated by one rank
+        w = workloads.Workload("rand", tp, T, H, seed=9000 + k, n_outlier=min(2, H),
+                               outlier_mult=(20.0, 100.0))
+        parts = [workloads.partial_bf16(w, r) for r in range(tp)]
+    xs = [dev_bf16(p) for p in parts]
+    codes, scales = mxc.quantize_batched(fg, xs)
+    out = mxc.dequant_reduce(fg, codes, scales, T, H)
+    out16 = mxc.dequant_reduce(fg, codes, scales, T, H, out_dtype=torch.bfloat16)
+    own_rank = k % tp
+    own = mxc.dequant_reduce_own(fg, own_rank, xs[own_rank], codes, scales)
+    fused = mxc.dequant_reduce_requantize(fg, codes, scales, T, H) if (T * H) % 32 == 0 else None
+    rq = mxc.requantize_chunk(fg, out, 1, 0)
+    torch.cuda.synchronize()
+    ocs, oss = zip(*[oracle_mod.quantize_bf16(fo, p) for p in parts])
+    for r in range(tp):
+        assert np.array_equal(host_scales(oracle_mod, fo, scales[r], oss[r].shape), oss[r])
+        assert np.array_equal(host(codes[r]).reshape(T, -1), oracle_mod.pack(fo, ocs[r]))
+    want = oracle_mod.dequant_reduce(fo, list(ocs), list(oss))
+    assert same_f32(host(out), want)
+    assert np.array_equal(host(out16.view(torch.int16)).view(np.uint16), oracle_mod.round_to_bf16(want))
+    want_own = oracle_mod.dequant_reduce_own(fo, own_rank, parts[own_rank], list(ocs), list(oss))
+    assert same_f32(host(own), want_own)
+    oc2, os2 = oracle_mod.quantize_f32(fo, want)
+    for got in ([rq] if fused is None else [rq, fused]):
+        assert np.array_equal(host_scales(oracle_mod, fo, got[1], os2.shape), os2)
+        assert np.array_equal(host(got[0]).reshape(T, -1), oracle_mod.pack(fo, oc2))

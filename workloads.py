@@ -115,3 +115,24 @@ def small_like(w: Workload, tokens: int, hidden: int) -> Workload:
     n_out = max(1, round(w.n_outlier * hidden / w.hidden)) if w.n_outlier else 0
     return Workload(f"{w.name}_as_{tokens}x{hidden}", w.tp, tokens, hidden, w.seed, w.body,
                     n_out, w.outlier_mult, w.formats, w.requantize)
+
+
+def stress_bf16(seed: int, tokens: int, hidden: int) -> np.ndarray:
+    """A tensor built to stress a quantizer rather than to look like activations: per-block
+    exponent ranges anywhere in bfloat16's span (subnormals and the largest binade included),
+    random signs, and a sprinkle of +-0, Inf and NaN.  uint16 bit patterns [tokens, hidden]."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    n = tokens * hidden
+    # a base exponent per group of 8 elements, a few bits of spread around it per element
+    base = rng.integers(0, 255, size=(n + 7) // 8)
+    spread = rng.integers(-6, 1, size=n)
+    expo = np.clip(np.repeat(base, 8)[:n] + spread, 0, 254).astype(np.uint16)
+    mant = rng.integers(0, 128, size=n).astype(np.uint16)
+    sign = rng.integers(0, 2, size=n).astype(np.uint16)
+    bits = (sign << np.uint16(15)) | (expo << np.uint16(7)) | mant
+    special = rng.random(n)
+    bits[special < 0.02] &= np.uint16(0x8000)                       # +-0
+    bits[(special >= 0.02) & (special < 0.021)] = np.uint16(0x7F80)  # +Inf
+    bits[(special >= 0.021) & (special < 0.022)] = np.uint16(0xFF80)  # -Inf
+    bits[(special >= 0.022) & (special < 0.023)] = np.uint16(0x7FC1)  # NaN
+    return bits.reshape(tokens, hidden)
