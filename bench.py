@@ -358,6 +358,31 @@ def main():
         nbw = N * (cbw + sbw) + cbw + sbw
         sweep["fused_reduce_requantize_whole_tensor"] = {
             "ms": ms, "hbm_GBps": nbw / ms / 1e6, "frac": nbw / ms / 1e6 / HBM_PEAK_GBS}
+        # the reduction as the paper's Profiling section words it: the worker's own partial raw,
+        # the other N-1 decoded, bf16 out (the dtype the next layer consumes); and the
+        # rank-consistent all-decoded form with bf16 out
+        # eight bf16 outputs (the two halves of each float32 buffer) keep the rotation at 512 MiB
+        outs16 = [o.view(-1).view(torch.bfloat16)[h * T * H:(h + 1) * T * H].view(T, H)
+                  for o in outs for h in (0, 1)]
+        NOUT16 = len(outs16)
+        for (fx, fy, fb, fs) in w.formats:
+            f = mxc.Format(fx, fy, fb, fs)
+            ps = [packed_set(f) for _ in range(R)]
+            for i in range(R):
+                mxc.quantize_batched(f, x_sets[0], *ps[i])
+            cbk, sbk = mxc.packed_sizes(f, T, H)
+            dl16 = [mxc.prepare_dequant_reduce(f, *ps[i % R], T, H, outs16[i % NOUT16])
+                    for i in range(2 * PERIOD)]
+            ms = time_calls(lambda i: dl16[i % (2 * PERIOD)]())
+            nb16 = N * (cbk + sbk) + T * H * 2
+            sweep[f"dequant_reduce_bf16_out_e{fx}m{fy}"] = {
+                "ms": ms, "hbm_GBps": nb16 / ms / 1e6, "frac": nb16 / ms / 1e6 / HBM_PEAK_GBS}
+            ms = time_calls(lambda i: mxc.dequant_reduce_own(
+                f, i % N, x_sets[i % 2][i % N], ps[i % R][0], ps[i % R][1], out=outs16[i % NOUT16]))
+            nbo = (N - 1) * (cbk + sbk) + T * H * 2 + T * H * 2
+            sweep[f"dequant_reduce_own_raw_bf16_out_e{fx}m{fy}"] = {
+                "ms": ms, "hbm_GBps": nbo / ms / 1e6, "frac": nbo / ms / 1e6 / HBM_PEAK_GBS}
+            del ps, dl16
         # the paper's own profiled input sizes are a few hundred tokens (Table 3: 2x64 ... 16x256):
         # one rank's quantize and the N-way reduce at 256 tokens, where a call is launch-bound
         f = mxc.Format(2, 1, 32, 8)
