@@ -643,13 +643,29 @@ __device__ __forceinline__ uint32_t bitselect(uint32_t m, uint32_t a, uint32_t b
 }
 
 // Four b-bit codes in the low 4b bits of f (bits above are ignored) -> four bytes
-// sign<<7 | magnitude.  Copy k of f, shifted left by k*(8-b), carries code k's magnitude at byte k
-// and code k-1's sign at bit 7 of byte k-1; four selects stitch the copies together and one mask
+// sign<<7 | magnitude.
+//
+// General form: copy k of f, shifted left by k*(8-b), carries code k's magnitude at byte k and
+// code k-1's sign at bit 7 of byte k-1; four selects stitch the copies together and one mask
 // clears what lies between magnitude and sign.
+//
+// 5-bit codes take fewer instructions with two 24-bit multiplies, each of which makes two shifted
+// copies at once: codes 0 and 2 (bits 0-4, 10-14) times 1 + 2^6 puts them at bits 0 and 16, codes
+// 1 and 3 (bits 5-9, 15-19) times 2^3 + 2^9 puts them at bits 8 and 24.  The unwanted cross
+// products land between the wanted fields (bits 6-15 and 14-23, carries included) and are dropped
+// by the byte permute and the masks that follow.
 template <class E>
 __device__ __forceinline__ uint32_t codes_to_bytes(uint32_t f)
 {
     constexpr int b = E::bits, g = 8 - E::bits;
+    if (b == 5) {
+        const uint32_t even = __umul24(f & 0x07C1Fu, (1u << 6) + 1u);
+        const uint32_t odd = __umul24(f & 0xF83E0u, (1u << 9) + (1u << 3));
+        // bytes 0 and 2 of `even`, bytes 1 and 3 of `odd`: code k in bits 0-4 of byte k (a byte
+        // permute, which the compiler keeps as one instruction; an and/or select it splits up)
+        const uint32_t c5 = __builtin_amdgcn_perm(odd, even, 0x07020500u);
+        return (c5 & 0x0F0F0F0Fu) | ((c5 << 3) & 0x80808080u);
+    }
     uint32_t r = f;
     r = bitselect((1u << (b - 1)) - 1u, r, f << g);
     r = bitselect((1u << (8 + b - 1)) - 1u, r, f << (2 * g));
