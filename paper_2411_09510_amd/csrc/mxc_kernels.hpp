@@ -837,7 +837,10 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
     __shared__ u32x4 tile[WG / 64][FUSED ? 1 : 64 * OC];
 
     const int lane = (int)(threadIdx.x & 63);
-    const int wave = (int)(threadIdx.x >> 6);
+    // the wave index is the same in every lane: telling the compiler so keeps wave_chunk0 and
+    // every base address derived from it in scalar registers, and the per-lane part of an
+    // address a 32-bit offset
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const size_t wave_chunk0 = ((size_t)blockIdx.x * (WG / 64) + (size_t)wave) * 64;
     const size_t chunk = wave_chunk0 + (size_t)lane;
     const size_t nchunks = a.units / 4;
@@ -858,7 +861,7 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
         for (int i = 0; i < RC; ++i) {
             const bool on = valid && (r0 + i < a.tp) && !(OWN && r0 + i == a.own_rank);
             const int r = min(r0 + i, a.tp - 1);
-            const uint32_t *cp = (const uint32_t *)a.codes[r] + chunk * W;
+            const uint32_t *cp = (const uint32_t *)a.codes[r] + wave_chunk0 * W + lane * W;
 #pragma unroll
             for (int k = 0; k < W; ++k) cw[i][k] = 0u;
             if (on) {
@@ -881,7 +884,7 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
             // NB scale bytes, little-endian in one register; idle lanes read as "e = 0"
             uint32_t sb = (uint32_t)sf.sbias * 0x01010101u;
             if (on && sf.sbits == 8) {
-                const uint8_t *sp = (const uint8_t *)a.scales[r] + chunk * NB;
+                const uint8_t *sp = (const uint8_t *)a.scales[r] + wave_chunk0 * NB + lane * NB;
                 if (NB == 1) sb = ld<NTL>(sp);
                 else if (NB == 2) sb = ld<NTL>((const uint16_t *)sp);
                 else sb = ld<NTL>((const uint32_t *)sp);
@@ -902,7 +905,7 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
                 // the lane's 32 bfloat16 values: 64 contiguous bytes
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
-                    const u32x4 raw = valid ? ld<NTL>((const u32x4 *)a.own_x + chunk * 4 + k)
+                    const u32x4 raw = valid ? ld<NTL>((const u32x4 *)a.own_x + wave_chunk0 * 4 + (lane * 4 + k))
                                             : u32x4{0u, 0u, 0u, 0u};
                     add_raw_bf16(raw, acc + 8 * k);
                 }
@@ -1030,7 +1033,7 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
             sbytes |= (uint32_t)sc << (8 * n);
         }
         if (valid) {
-            uint32_t *cp = (uint32_t *)a.codes_out + chunk * W;
+            uint32_t *cp = (uint32_t *)a.codes_out + wave_chunk0 * W + lane * W;
             if (W == 4) {
                 st<NTS>((u32x4 *)cp, u32x4{cw[0], cw[1], cw[2], cw[3 < W ? 3 : 0]});
             } else if (W == 6) {
@@ -1043,7 +1046,7 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
                 for (int k = 0; k < W; ++k) st<NTS>(cp + k, cw[k]);
             }
             if (sf.sbits == 8) {
-                uint8_t *sp = (uint8_t *)a.scales_out + chunk * NB;
+                uint8_t *sp = (uint8_t *)a.scales_out + wave_chunk0 * NB + lane * NB;
                 if (NB == 1) *sp = (uint8_t)sbytes;
                 else if (NB == 2) *(uint16_t *)sp = (uint16_t)sbytes;
                 else *(uint32_t *)sp = sbytes;
