@@ -611,6 +611,39 @@ def test_round_to_bf16_matches_library_conversion(oracle_mod):
     assert np.all(got[nan] == 0x7FC0)
 
 
+@pytest.mark.parametrize("x,y,f8", [(1, 2, "float8_e5m2"), (2, 2, "float8_e5m2"), (3, 2, "float8_e5m2"),
+                                    (1, 3, "float8_e4m3fn"), (2, 3, "float8_e4m3fn")])
+def test_element_rounding_against_library_float8_casts(oracle_mod, x, y, f8):
+    """A format with 2 (3) mantissa bits is the low end of the code space of the 8-bit float
+    E5M2 (E4M3): scaled so that the smallest normals coincide, rounding to the element format and
+    the library's round-to-nearest-even cast to that 8-bit float pick the same code wherever the
+    element format does not saturate.  This pins rounding, ties and subnormals of the oracle to
+    a routine it shares nothing with."""
+    import torch
+    dt = getattr(torch, f8)
+    hw_bias = 15 if f8 == "float8_e5m2" else 7
+    B = 32
+    fmt = oracle_mod.Format(x, y, B, 8)
+    beta = 2 ** (x - 1) - 1
+    magmask = 2 ** (x + y) - 1
+    rng = np.random.default_rng(100 * x + y)
+    # float32 inputs with full 24-bit significands, block maxima in assorted binades
+    v = (rng.standard_normal((64, 16 * B)) * np.exp2(rng.integers(-20, 20, size=(64, 1)))).astype(np.float32)
+    v[:, ::7] *= np.float32(0.03125)                       # plenty of values in the subnormal range
+    codes, scales = oracle_mod.quantize_f32(fmt, v)
+    e = scales.astype(np.int64) - 127
+    p = v.astype(np.float64) * np.exp2(-np.repeat(e, B, axis=1).astype(np.float64))   # exact
+    q = torch.from_numpy(p * 2.0 ** (beta - hw_bias)).to(torch.float32)               # exact: power of two
+    byte = q.to(dt).view(torch.uint8).numpy()
+    lib_mag, lib_sign = byte & 0x7F, byte >> 7
+    mag, sign = codes & magmask, codes >> (x + y)
+    assert np.array_equal(sign, lib_sign)
+    inside = lib_mag <= magmask
+    assert inside.mean() > 0.9
+    assert np.array_equal(mag[inside], lib_mag[inside])
+    assert np.all(mag[~inside] == magmask)                 # beyond the element format: saturated
+
+
 # ----------------------------------------------------------------------- generators ---------
 
 def test_workload_generators_are_seeded_and_shaped():
