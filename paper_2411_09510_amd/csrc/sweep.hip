@@ -4,6 +4,9 @@
 //
 //   mxc_sweep [tokens] [hidden]        default 4096 8192, always 8 partials, block 32, E8M0 scale
 //
+// Besides the variants it times two probes that move the bytes of the 4-bit quantizer and of the
+// 4-bit tile reduce in the same pattern without any arithmetic: the ceiling of each memory shape.
+//
 // Every variant is launched 20 times back to back over three rotating buffer sets (so that no
 // launch reads what the previous one left in the last-level cache); the best of five such runs is
 // printed as microseconds per launch, GB/s of algorithmic bytes and fraction of the 8 TB/s peak.
@@ -213,6 +216,62 @@ static void copy()
     report(what, ms, 2.0 * n * 4.0);
 }
 
+
+// Traffic of the 4-bit tile reduce without its arithmetic: per lane and rank one 16-byte code
+// load and one scale byte, per lane eight 16-byte stores laid out as the reduce kernel's
+// (contiguous 1 KiB per store instruction).  What it reaches is the ceiling of that memory
+// shape on this GPU.
+__global__ __launch_bounds__(256) void reduce_shape_probe(ReduceArgs a)
+{
+    const int lane = (int)(threadIdx.x & 63);
+    const size_t tile = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const size_t chunk = tile * 64 + (size_t)lane;
+    if (chunk >= a.units / 4) return;
+    u32x4 c[8];
+    uint32_t s = 0;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        c[r] = __builtin_nontemporal_load((const u32x4 *)a.codes[r] + chunk);
+        s += __builtin_nontemporal_load((const uint8_t *)a.scales[r] + chunk);
+    }
+    u32x4 *out = (u32x4 *)a.out + tile * 512;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        c[r].x ^= s;
+        __builtin_nontemporal_store(c[r], out + r * 64 + lane);
+    }
+}
+
+// Traffic of the 4-bit quantizer without its arithmetic: per lane a 16-byte bf16 load and a
+// 4-byte store, one scale byte per four lanes, all eight partials in one launch.
+__global__ __launch_bounds__(256) void quantize_shape_probe(QuantArgs a)
+{
+    const size_t unit0 = ((size_t)blockIdx.x * 256 + threadIdx.x) * 2 - (threadIdx.x & 63);
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const size_t unit = unit0 + (size_t)u * 64;
+        if (unit >= a.units) continue;
+        const u32x4 v = __builtin_nontemporal_load((const u32x4 *)a.x[blockIdx.y] + unit);
+        const uint32_t w = v.x ^ v.y ^ v.z ^ v.w;
+        __builtin_nontemporal_store(w, (uint32_t *)a.codes[blockIdx.y] + unit);
+        if ((threadIdx.x & 3) == 0) ((uint8_t *)a.scales[blockIdx.y])[unit / 4] = (uint8_t)w;
+    }
+}
+
+static void shape_probes()
+{
+    double ms = best_ms([&](int i) {
+        ReduceArgs a = rargs(i, 4);
+        hipLaunchKernelGGL(reduce_shape_probe, dim3((unsigned)((units / 4 + 255) / 256)), dim3(256), 0, 0, a);
+    });
+    report("traffic of the 4-bit tile reduce, no arithmetic", ms, N * (n / 2.0 + n / 32.0) + n * 4.0);
+    ms = best_ms([&](int i) {
+        QuantArgs a = qargs(i, 4);
+        hipLaunchKernelGGL(quantize_shape_probe, dim3((unsigned)((units + 511) / 512), N), dim3(256), 0, 0, a);
+    });
+    report("traffic of the 4-bit quantizer, no arithmetic", ms, N * (n * 2.0 + n / 2.0 + n / 32.0));
+}
+
 int main(int argc, char **argv)
 {
     if (argc > 1) T = (size_t)std::atoll(argv[1]);
@@ -263,6 +322,7 @@ int main(int argc, char **argv)
         return 0;
     }
     copy<1, false>(); copy<4, false>(); copy<4, true>();
+    shape_probes();
     quant<2, 1, 1, false, false>(); quant<2, 1, 2, false, false>(); quant<2, 1, 4, false, false>();
     quant<2, 1, 2, true, false>(); quant<2, 1, 1, true, true>(); quant<2, 1, 2, true, true>();
     quant<2, 1, 4, true, true>();
