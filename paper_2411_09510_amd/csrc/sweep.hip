@@ -1,5 +1,5 @@
 // mxc_sweep — times template variants of the library's kernels on one GPU, so that the launch
-// shapes chosen in mxc.hip can be re-checked (or re-tuned on other hardware).  Timing only: the
+// shapes chosen in mxc_dispatch.hpp can be re-checked (or re-tuned on other hardware).  Timing only: the
 // inputs are pseudo-random bits, results are not inspected.
 //
 //   mxc_sweep [tokens] [hidden]        default 4096 8192, always 8 partials, block 32, E8M0 scale
