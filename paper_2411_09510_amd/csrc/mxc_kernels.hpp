@@ -854,6 +854,35 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
 #pragma unroll
     for (int n = 0; n < NB; ++n) poisoned[n] = false;
 
+    // OWN: the lane's 32 raw bfloat16 values are 64 contiguous bytes.  The wave loads its 4 KiB
+    // as contiguous 16-byte pieces and hands each lane its four through the LDS tile (free until
+    // the output exchange), instead of four loads per lane that each touch 64 different lines.
+    u32x4 own[4];
+    if (OWN) {
+        u32x4 *t = tile[FUSED ? 0 : wave];
+        const u32x4 *src = (const u32x4 *)a.own_x + wave_chunk0 * 4;
+        const size_t own_pieces = wave_chunk0 < nchunks ? (nchunks - wave_chunk0) * 4 : 0;
+        u32x4 pv[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int g = k * 64 + lane;         // piece index within the wave's 4 KiB
+            pv[k] = (size_t)g < own_pieces ? ld<NTL>(src + g) : u32x4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int g = k * 64 + lane;
+            const int l = g >> 2, c = g & 3;     // owner lane and its piece number
+            t[l * 4 + ((c + l) & 3)] = pv[k];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int c = 0; c < 4; ++c) own[c] = t[lane * 4 + ((c + lane) & 3)];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+
     for (int r0 = 0; r0 < a.tp; r0 += RC) {
         uint32_t cw[RC][W];
         uint32_t sw[RC];
@@ -902,13 +931,8 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
 #pragma unroll
         for (int i = 0; i < RC; ++i) {
             if (OWN && r0 + i == a.own_rank) {
-                // the lane's 32 bfloat16 values: 64 contiguous bytes
 #pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const u32x4 raw = valid ? ld<NTL>((const u32x4 *)a.own_x + wave_chunk0 * 4 + (lane * 4 + k))
-                                            : u32x4{0u, 0u, 0u, 0u};
-                    add_raw_bf16(raw, acc + 8 * k);
-                }
+                for (int k = 0; k < 4; ++k) add_raw_bf16(own[k], acc + 8 * k);
             } else if (r0 + i < a.tp) {
 #pragma unroll
                 for (int n = 0; n < NB; ++n) {
