@@ -51,23 +51,5 @@ def build(force: bool = True) -> str:
     return LIB
 
 
-SWEEP_SRC = os.path.join(HERE, "csrc", "sweep.hip")
-SWEEP_BIN = os.path.join(HERE, "mxc_sweep")
-
-
-def build_sweep() -> str:
-    """Compile the variant-timing tool ``mxc_sweep`` (optional; the library does not need it)."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    flags = [f for f in HIPCC_FLAGS if f != "-fPIC"]
-    cmd = [hipcc, *flags, "-I", os.path.join(ROOT, "include"), "-o", SWEEP_BIN, SWEEP_SRC]
-    proc = subprocess.run(cmd, capture_output=True, text=True)
-    if proc.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + proc.stdout + proc.stderr)
-    return SWEEP_BIN
-
-
 if __name__ == "__main__":
-    import sys
     print(build())
-    if "--sweep" in sys.argv:
-        print(build_sweep())

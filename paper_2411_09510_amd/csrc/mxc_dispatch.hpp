@@ -25,10 +25,20 @@ constexpr int kReduceRC = 8;        // ranks loaded together, unit form
 // nontemporal stores: measured 5 % faster than plain ones whenever the outputs of successive
 // calls do not all fit the 256 MB last-level cache
 constexpr bool kReduceNTL = true, kReduceNTS = true;
-// ranks loaded together, tile form (measured: 4 is best or within noise of best for 4-, 5- and
-// 6-bit codes)
-constexpr int kTileRC = 4;
-constexpr int kFusedRC = 8;         // no LDS tile and a read-dominated stream: all ranks in flight
+// Tile-form reduce: ranks whose loads are issued together (rc) and how 3-, 5- and 6-bit codes are
+// fetched (stage: 0 = each lane loads its own dwords, 1 = contiguous 128-bit loads redistributed
+// through LDS, 2 = the same with loads that write LDS directly), per code width and kernel form,
+// each the fastest measured at the Llama-70B-shaped configuration (tp 8, 4096 x 8192).
+struct TileShape {
+    int rc, stage;
+};
+constexpr TileShape tile_shape(int code_bits, bool out_bf16, bool fused, bool own)
+{
+    if (code_bits == 4) return {8, 0};
+    if (code_bits == 5) return (fused || own) ? TileShape{8, 0} : TileShape{2, 2};
+    if (code_bits == 6) return (!out_bf16 && !fused && !own) ? TileShape{8, 2} : TileShape{4, 2};
+    return {4, 2};
+}
 constexpr int kCopyU = 1;
 constexpr bool kHw = true;          // use the scaled-conversion instructions where exact
 
@@ -117,8 +127,9 @@ int reduce_any(const mxc_format *f, const ReduceArgs &a, hipStream_t st)
             // whole 32-element chunks: one lane per chunk, output staged through LDS
             const size_t chunks = a.units / 4;
             const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads));
-            return launch(dequant_reduce_tile_kernel<E, B, OUT_BF16, kTileRC, kReduceNTL,
-                                                     kReduceNTS, kHw, false, OWN>,
+            constexpr TileShape ts = tile_shape(E::bits, OUT_BF16, false, OWN);
+            return launch(dequant_reduce_tile_kernel<E, B, OUT_BF16, ts.rc, kReduceNTL, kReduceNTS, kHw,
+                                                     false, OWN, kThreads, ts.stage>,
                           grid, st, a);
         }
         // sizes that are not a multiple of 32 elements (only possible with blocks of 8 or 16)

@@ -819,279 +819,226 @@ __device__ __forceinline__ uint32_t stream_bits_rt(const uint32_t (&s)[NW], int 
 // codes are 4b contiguous bytes per rank (a single 128-bit load for 4-bit codes), its scales 1, 2
 // or 4 contiguous bytes per rank, so every load instruction of the wave is contiguous and as wide
 // as the format allows.  The lane's 32 sums are then exchanged through a wave-private LDS tile so
-// that the wave writes its 8 KiB (4 KiB for bf16) of output as contiguous 128-bit stores.
+// that the wave writes its 8 KiB (4 KiB for bf16) of output as contiguous 128-bit stores.  A wave
+// tile is the 64 chunks of one wave.
 
-// FUSED: instead of storing the sums, quantize them again in the lane that holds them (same
-// rule as the quantizer applied to binary32 input) and store codes and scales; bit-identical to
-// running the unfused kernels one after the other.
-// WG: threads per workgroup (a multiple of 64; each wave works on its own).
-template <class E, int B, bool OUT_BF16, int RC, bool NTL, bool NTS, bool HW, bool FUSED = false,
-          bool OWN = false, int WG = kThreads>
-__global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
+// What a lane fetches for one rank of its chunk: W dwords of codes and the chunk's scale codes,
+// one per byte.
+template <int W>
+struct ChunkBits {
+    uint32_t cw[W];
+    uint32_t sw;
+};
+
+// Loads the lane's share of one rank's arrays for the wave tile that starts at chunk
+// `wave_chunk0`.  A lane that is not `on` (past the end, a rank beyond tp, the own rank of the OWN
+// form) loads nothing and reads as code 0 with "e = 0".  STAGED: the codes of a full wave tile
+// (`full`) are left to load_codes_staged and only the scales are loaded here.
+template <class E, int B, bool NTL, bool STAGED = false>
+__device__ __forceinline__ void load_chunk(ChunkBits<E::bits> &c, const void *codes, const void *scales,
+                                           size_t wave_chunk0, int lane, bool on, const ScaleFmt &sf,
+                                           size_t nchunks, bool full = false)
 {
-    constexpr int NB = 32 / B;                   // blocks (scales) per chunk
-    constexpr int W = E::bits;                   // dwords of codes per chunk
+    constexpr int W = E::bits, NB = 32 / B;
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    const uint32_t *cp = (const uint32_t *)codes + wave_chunk0 * W + lane * W;
+#pragma unroll
+    for (int k = 0; k < W; ++k) c.cw[k] = 0u;
+    if (on && !(STAGED && full)) {
+        if (W == 4) {
+            const u32x4 v = ld<NTL>((const u32x4 *)cp);
+            c.cw[0] = v.x; c.cw[1] = v.y; c.cw[2] = v.z; c.cw[3 < W ? 3 : 0] = v.w;
+        } else if (W == 6) {
+#pragma unroll
+            for (int k = 0; k < 3; ++k) {
+                const u32x2 v = ld<NTL>((const u32x2 *)cp + k);
+                c.cw[(2 * k) < W ? 2 * k : 0] = v.x;
+                c.cw[(2 * k + 1) < W ? 2 * k + 1 : 0] = v.y;
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < W; ++k) c.cw[k] = ld<NTL>(cp + k);
+        }
+    }
+    // NB scale bytes, little-endian in one register; idle lanes read as "e = 0"
+    uint32_t sb = (uint32_t)sf.sbias * 0x01010101u;
+    if (on && sf.sbits == 8) {
+        const uint8_t *sp = (const uint8_t *)scales + wave_chunk0 * NB + lane * NB;
+        if (NB == 1) sb = ld<NTL>(sp);
+        else if (NB == 2) sb = ld<NTL>((const uint16_t *)sp);
+        else sb = ld<NTL>((const uint32_t *)sp);
+    } else if (on) {
+        // packed stream: NB fields of s bits, re-spread to one byte each
+        const size_t chunk = wave_chunk0 + (size_t)lane;
+        const uint32_t raw = load_bits((const uint8_t *)scales, chunk * NB * (size_t)sf.sbits,
+                                       NB * sf.sbits, (nchunks * NB * (size_t)sf.sbits + 7) >> 3);
+        sb = 0;
+#pragma unroll
+        for (int n = 0; n < NB; ++n)
+            sb |= ((raw >> (n * sf.sbits)) & ((1u << sf.sbits) - 1u)) << (8 * n);
+    }
+    c.sw = sb;
+}
+
+// 32 five-bit codes (5 dwords of the bit stream) -> 32 six-bit slots (6 dwords), slot = code << 1.
+// Four codes at a time: their 20 bits are taken one position up (bits 1..20), codes 2 and 3 move
+// two positions up by adding three times their own bits (low part + 4 * high part), codes 1 and 3
+// one more by adding themselves; the resulting 24-bit pieces are whole bytes of the slot stream,
+// which three byte permutes per four pieces put together.
+__device__ __forceinline__ void widen_5_to_6(const uint32_t (&in)[5], uint32_t (&out)[6])
+{
+    uint32_t p[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int pos = 20 * q - 1;              // stream bit that lands on bit 0 (constant)
+        uint32_t x;
+        if (q == 0) {
+            x = in[0] << 1;
+        } else {
+            const int wd = pos >> 5, off = pos & 31;
+            x = in[wd] >> off;
+            if (off + 21 > 32) x |= in[wd + 1 < 5 ? wd + 1 : wd] << (32 - off);
+        }
+        x &= 0x1FFFFEu;
+        const uint32_t t = x & 0x1FF800u;        // codes 2 and 3
+        x = __umul24(t, 3u) + x;
+        const uint32_t u = x & ((0x1Fu << 6) | (0x1Fu << 18));   // codes 1 and 3
+        p[q] = x + u;
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        out[3 * k + 0] = __builtin_amdgcn_perm(p[4 * k + 1], p[4 * k + 0], 0x04020100u);
+        out[3 * k + 1] = __builtin_amdgcn_perm(p[4 * k + 2], p[4 * k + 1], 0x05040201u);
+        out[3 * k + 2] = __builtin_amdgcn_perm(p[4 * k + 3], p[4 * k + 2], 0x06050402u);
+    }
+}
+
+// Decodes one rank's chunk and adds it to the lane's 32 sums; notes blocks marked non-finite.
+template <class E, int B, bool HW>
+__device__ __forceinline__ void add_chunk(const ChunkBits<E::bits> &c, const ScaleFmt &sf, float (&acc)[32],
+                                          bool (&poisoned)[32 / B])
+{
+    constexpr int W = E::bits, NB = 32 / B;
     constexpr bool kHw = HW && E::hw != HW_NONE;
-    constexpr int OC = OUT_BF16 ? 4 : 8;         // 16-byte output pieces per lane
-    constexpr bool kChunkBf6 = E::x == 3 && E::y == 2 && B == 32;   // chunk = one hardware BF6 block
-    __shared__ u32x4 tile[WG / 64][FUSED ? 1 : 64 * OC];
-
-    const int lane = (int)(threadIdx.x & 63);
-    // the wave index is the same in every lane: telling the compiler so keeps wave_chunk0 and
-    // every base address derived from it in scalar registers, and the per-lane part of an
-    // address a 32-bit offset
-    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const size_t wave_chunk0 = ((size_t)blockIdx.x * (WG / 64) + (size_t)wave) * 64;
-    const size_t chunk = wave_chunk0 + (size_t)lane;
-    const size_t nchunks = a.units / 4;
-    const bool valid = chunk < nchunks;
-    const ScaleFmt sf = a.sf;
-
-    float acc[32];
+    // the chunk is one block of a hardware 6-bit format: BF6 = E3M2; FP6 = E2M3, of which E2M2
+    // is the half with an even mantissa (same bias, same largest exponent: 6-bit code = 5-bit
+    // code << 1)
+    constexpr bool kChunkBf6 = E::x == 3 && E::y == 2 && B == 32;
+    constexpr bool kChunkFp6 = E::x == 2 && (E::y == 2 || E::y == 3) && B == 32;
+    constexpr bool kChunk6 = kChunkBf6 || kChunkFp6;
 #pragma unroll
-    for (int j = 0; j < 32; ++j) acc[j] = kFoldStart;
-    bool poisoned[NB];
+    for (int n = 0; n < NB; ++n) {
+        const int sc = (int)((c.sw >> (8 * n)) & 0xFFu);
+        const int e = sc - sf.sbias;
+        poisoned[n] = poisoned[n] || (sf.has_nan && sc == 255);
+        const int field = kChunk6 ? e + 127 : e - E::beta + E::hw_bias + 127;
+        const bool ok = field >= 0 && field <= 254;
+        float d[B];
+        if (kHw && kChunk6 && __builtin_amdgcn_ballot_w64(!ok) == 0) {
+            // the lane holds one whole hardware block: a single instruction decodes the 32 codes
+            uint32_t s6[6];
+            if (W == 5) {
+                const uint32_t in5[5] = {c.cw[0], c.cw[1], c.cw[2], c.cw[3 < W ? 3 : 0], c.cw[4 < W ? 4 : 0]};
+                widen_5_to_6(in5, s6);
+            } else {
 #pragma unroll
-    for (int n = 0; n < NB; ++n) poisoned[n] = false;
-
-    // OWN: the lane's 32 raw bfloat16 values are 64 contiguous bytes.  The wave loads its 4 KiB
-    // as contiguous 16-byte pieces and hands each lane its four through the LDS tile (free until
-    // the output exchange), instead of four loads per lane that each touch 64 different lines.
-    u32x4 own[4];
-    if (OWN) {
-        u32x4 *t = tile[FUSED ? 0 : wave];
-        const u32x4 *src = (const u32x4 *)a.own_x + wave_chunk0 * 4;
-        const size_t own_pieces = wave_chunk0 < nchunks ? (nchunks - wave_chunk0) * 4 : 0;
-        u32x4 pv[4];
+                for (int k = 0; k < 6; ++k) s6[k] = c.cw[k < W ? k : 0];
+            }
+            const u32x6 src = {s6[0], s6[1], s6[2], s6[3], s6[4], s6[5]};
+            // inline assembly with an early-clobber result: through the builtin the register
+            // allocator let the result registers overlap the per-lane scale register
+            f32x32 r;
+            const float hs6 = __uint_as_float((uint32_t)field << 23);
+            if (kChunkBf6)
+                asm("v_cvt_scalef32_pk32_f32_bf6 %0, %1, %2" : "=&v"(r) : "v"(src), "v"(hs6));
+            else
+                asm("v_cvt_scalef32_pk32_f32_fp6 %0, %1, %2" : "=&v"(r) : "v"(src), "v"(hs6));
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int g = k * 64 + lane;         // piece index within the wave's 4 KiB
-            pv[k] = (size_t)g < own_pieces ? ld<NTL>(src + g) : u32x4{0u, 0u, 0u, 0u};
+            for (int j = 0; j < B; ++j) d[j] = r[j < 32 ? j : 0];
+        } else if (kHw && __builtin_amdgcn_ballot_w64(!ok) == 0) {
+            const float hs = __uint_as_float((uint32_t)field << 23);
+            // B codes of block n, eight at a time
+#pragma unroll
+            for (int g = 0; g < B / 8; ++g) {
+                // the 8 codes occupy 8b bits starting at bit first*b (positions are constants once
+                // n and g are unrolled)
+                const int first = n * B + g * 8;
+                const uint32_t lo = stream_bits_rt<W>(c.cw, first * W, 4 * W);
+                const uint32_t hi = stream_bits_rt<W>(c.cw, first * W + 4 * W, 4 * W);
+                const uint64_t v8 = (uint64_t)lo | ((uint64_t)hi << (4 * W));
+                float d8[8];
+                decode_unit_hw<E>(v8, hs, d8);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) d[g * 8 + j] = d8[j];
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < B; ++j) {
+                const uint32_t cj = stream_bits_rt<W>(c.cw, (n * B + j) * W, W);
+                const uint32_t bits = ((cj & E::magmask) << (23 - E::y)) | ((cj >> (E::x + E::y)) << 31);
+                d[j] = ldexpf(__uint_as_float(bits), e + 127 - E::beta);
+            }
         }
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int g = k * 64 + lane;
-            const int l = g >> 2, c = g & 3;     // owner lane and its piece number
-            t[l * 4 + ((c + l) & 3)] = pv[k];
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-        for (int c = 0; c < 4; ++c) own[c] = t[lane * 4 + ((c + lane) & 3)];
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
+        for (int j = 0; j < B; ++j) acc[n * B + j] += d[j];
     }
+}
 
-    for (int r0 = 0; r0 < a.tp; r0 += RC) {
-        uint32_t cw[RC][W];
-        uint32_t sw[RC];
+// Blocks that some rank marked non-finite become NaN.
+template <int B>
+__device__ __forceinline__ void apply_poison(float (&acc)[32], const bool (&poisoned)[32 / B])
+{
 #pragma unroll
-        for (int i = 0; i < RC; ++i) {
-            const bool on = valid && (r0 + i < a.tp) && !(OWN && r0 + i == a.own_rank);
-            const int r = min(r0 + i, a.tp - 1);
-            const uint32_t *cp = (const uint32_t *)a.codes[r] + wave_chunk0 * W + lane * W;
-#pragma unroll
-            for (int k = 0; k < W; ++k) cw[i][k] = 0u;
-            if (on) {
-                typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-                if (W == 4) {
-                    const u32x4 v = ld<NTL>((const u32x4 *)cp);
-                    cw[i][0] = v.x; cw[i][1] = v.y; cw[i][2] = v.z; cw[i][3 < W ? 3 : 0] = v.w;
-                } else if (W == 6) {
-#pragma unroll
-                    for (int k = 0; k < 3; ++k) {
-                        const u32x2 v = ld<NTL>((const u32x2 *)cp + k);
-                        cw[i][(2 * k) < W ? 2 * k : 0] = v.x;
-                        cw[i][(2 * k + 1) < W ? 2 * k + 1 : 0] = v.y;
-                    }
-                } else {
-#pragma unroll
-                    for (int k = 0; k < W; ++k) cw[i][k] = ld<NTL>(cp + k);
-                }
-            }
-            // NB scale bytes, little-endian in one register; idle lanes read as "e = 0"
-            uint32_t sb = (uint32_t)sf.sbias * 0x01010101u;
-            if (on && sf.sbits == 8) {
-                const uint8_t *sp = (const uint8_t *)a.scales[r] + wave_chunk0 * NB + lane * NB;
-                if (NB == 1) sb = ld<NTL>(sp);
-                else if (NB == 2) sb = ld<NTL>((const uint16_t *)sp);
-                else sb = ld<NTL>((const uint32_t *)sp);
-            } else if (on) {
-                // packed stream: NB fields of s bits, re-spread to one byte each
-                const uint32_t raw = load_bits((const uint8_t *)a.scales[r], chunk * NB * (size_t)sf.sbits,
-                                               NB * sf.sbits, (nchunks * NB * (size_t)sf.sbits + 7) >> 3);
-                sb = 0;
-#pragma unroll
-                for (int n = 0; n < NB; ++n)
-                    sb |= ((raw >> (n * sf.sbits)) & ((1u << sf.sbits) - 1u)) << (8 * n);
-            }
-            sw[i] = sb;
-        }
-#pragma unroll
-        for (int i = 0; i < RC; ++i) {
-            if (OWN && r0 + i == a.own_rank) {
-#pragma unroll
-                for (int k = 0; k < 4; ++k) add_raw_bf16(own[k], acc + 8 * k);
-            } else if (r0 + i < a.tp) {
-#pragma unroll
-                for (int n = 0; n < NB; ++n) {
-                    const int sc = (int)((sw[i] >> (8 * n)) & 0xFFu);
-                    const int e = sc - sf.sbias;
-                    poisoned[n] = poisoned[n] || (sf.has_nan && sc == 255);
-                    const int field = kChunkBf6 ? e + 127 : e - E::beta + E::hw_bias + 127;
-                    const bool ok = field >= 0 && field <= 254;
-                    float d[B];
-                    if (kHw && kChunkBf6 && __builtin_amdgcn_ballot_w64(!ok) == 0) {
-                        // E3M2 is the hardware's 6-bit BF6 and the lane holds one whole block:
-                        // a single instruction decodes the 32 codes
-                        const u32x6 src = {cw[i][0], cw[i][1], cw[i][2], cw[i][3 < W ? 3 : 0],
-                                           cw[i][4 < W ? 4 : 0], cw[i][5 < W ? 5 : 0]};
-                        // inline assembly with an early-clobber result, for the reason given at
-                        // the matching encode below (result registers must not overlap the scale)
-                        f32x32 r;
-                        const float hs6 = __uint_as_float((uint32_t)field << 23);
-                        asm("v_cvt_scalef32_pk32_f32_bf6 %0, %1, %2" : "=&v"(r) : "v"(src), "v"(hs6));
-#pragma unroll
-                        for (int j = 0; j < B; ++j) d[j] = r[j < 32 ? j : 0];
-                    } else if (kHw && __builtin_amdgcn_ballot_w64(!ok) == 0) {
-                        const float hs = __uint_as_float((uint32_t)field << 23);
-                        // B codes of block n, eight at a time
-#pragma unroll
-                        for (int g = 0; g < B / 8; ++g) {
-                            // the 8 codes occupy 8b bits starting at bit first*b (positions
-                            // are constants once n and g are unrolled)
-                            const int first = n * B + g * 8;
-                            const uint32_t lo = stream_bits_rt<W>(cw[i], first * W, 4 * W);
-                            const uint32_t hi = stream_bits_rt<W>(cw[i], first * W + 4 * W, 4 * W);
-                            const uint64_t v8 = (uint64_t)lo | ((uint64_t)hi << (4 * W));
-                            float d8[8];
-                            decode_unit_hw<E>(v8, hs, d8);
-#pragma unroll
-                            for (int j = 0; j < 8; ++j) d[g * 8 + j] = d8[j];
-                        }
-                    } else {
-#pragma unroll
-                        for (int j = 0; j < B; ++j) {
-                            const uint32_t c = stream_bits_rt<W>(cw[i], (n * B + j) * W, W);
-                            const uint32_t bits = ((c & E::magmask) << (23 - E::y)) |
-                                                  ((c >> (E::x + E::y)) << 31);
-                            d[j] = ldexpf(__uint_as_float(bits), e + 127 - E::beta);
-                        }
-                    }
-#pragma unroll
-                    for (int j = 0; j < B; ++j) acc[n * B + j] += d[j];
-                }
-            }
-        }
-    }
-#pragma unroll
-    for (int n = 0; n < NB; ++n)
+    for (int n = 0; n < 32 / B; ++n)
         if (poisoned[n]) {
 #pragma unroll
             for (int j = 0; j < B; ++j) acc[n * B + j] = __uint_as_float(0x7FC00000u);
         }
+}
 
-    if (FUSED) {
-        // The lane holds whole blocks: block maximum, scale and codes need no other lane.
-        uint32_t cw[W];
+// The own rank's raw bfloat16 values of a wave tile: the lane's 32 values are 64 contiguous
+// bytes; the wave loads its 4 KiB as contiguous 16-byte pieces (load_raw_pieces) and hands each
+// lane its four through the wave's LDS tile (take_raw_chunk), instead of four loads per lane that
+// each touch 64 different lines.
+template <bool NTL>
+__device__ __forceinline__ void load_raw_pieces(u32x4 (&pv)[4], const void *own_x, size_t wave_chunk0,
+                                                int lane, size_t nchunks)
+{
+    const u32x4 *src = (const u32x4 *)own_x + wave_chunk0 * 4;
+    const size_t own_pieces = wave_chunk0 < nchunks ? (nchunks - wave_chunk0) * 4 : 0;
 #pragma unroll
-        for (int k = 0; k < W; ++k) cw[k] = 0u;
-        uint32_t sbytes = 0;
-#pragma unroll
-        for (int n = 0; n < NB; ++n) {
-            uint32_t m = 0;
-#pragma unroll
-            for (int j = 0; j < B; ++j) m = max(m, __float_as_uint(acc[n * B + j]) & 0x7FFFFFFFu);
-            const int expfield = (int)(m >> 23);
-            int sc = 0;
-            if (kHw && kChunkBf6) {
-                // one instruction rounds the lane's 32 sums to BF6 = E3M2 (same scale rule)
-                const int unclamped = expfield - 127 - E::emax + sf.sbias;
-                const bool finite = expfield != 255;
-                sc = finite ? min(max(unclamped, 0), sf.smax) : sf.nonfinite;
-                const int fld = sc - sf.sbias + 127;
-                if (__builtin_amdgcn_ballot_w64(finite && (fld < 0 || fld > 254)) == 0) {
-                    // the instruction interleaves its two sources: result code 2j comes from
-                    // the first operand's element j, code 2j+1 from the second operand's
-                    f32x16 even, odd;
-#pragma unroll
-                    for (int j = 0; j < 16; ++j) {
-                        even[j] = acc[2 * j];
-                        odd[j] = acc[2 * j + 1];
-                    }
-                    // Issued as inline assembly with an early-clobber result: through the builtin
-                    // the register allocator let the six result registers overlap the per-lane
-                    // scale register, and every code after the first two came out wrong.
-                    u32x6 q;
-                    const float hs = __uint_as_float((uint32_t)max(fld, 0) << 23);
-                    asm("v_cvt_scalef32_2xpk16_bf6_f32 %0, %1, %2, %3"
-                        : "=&v"(q)
-                        : "v"(even), "v"(odd), "v"(hs));
-#pragma unroll
-                    for (int k = 0; k < W; ++k) cw[k] = finite ? q[k < 6 ? k : 0] : 0u;
-                    sbytes |= (uint32_t)sc << (8 * n);
-                    continue;
-                }
-            }
-#pragma unroll
-            for (int g = 0; g < B / 8; ++g) {
-                const int first = n * B + g * 8;
-                u32x4 w2[2];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    w2[0][j] = __float_as_uint(acc[first + j]);
-                    w2[1][j] = __float_as_uint(acc[first + 4 + j]);
-                }
-                const uint64_t packed = encode_unit<E, true, HW>(w2, expfield, sf, &sc);
-                // 8b bits at bit first*b of the chunk's stream (constant positions)
-                const int pos = first * W;
-                cw[pos >> 5] |= (uint32_t)(packed << (pos & 31));
-                if ((pos & 31) + 8 * W > 32) {
-                    const uint64_t rest = packed >> (32 - (pos & 31));
-                    cw[((pos >> 5) + 1) < W ? (pos >> 5) + 1 : 0] |= (uint32_t)rest;
-                    if ((pos & 31) + 8 * W > 64)
-                        cw[((pos >> 5) + 2) < W ? (pos >> 5) + 2 : 0] |= (uint32_t)(rest >> 32);
-                }
-            }
-            sbytes |= (uint32_t)sc << (8 * n);
-        }
-        if (valid) {
-            uint32_t *cp = (uint32_t *)a.codes_out + wave_chunk0 * W + lane * W;
-            if (W == 4) {
-                st<NTS>((u32x4 *)cp, u32x4{cw[0], cw[1], cw[2], cw[3 < W ? 3 : 0]});
-            } else if (W == 6) {
-                typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-#pragma unroll
-                for (int k = 0; k < 3; ++k)
-                    st<NTS>((u32x2 *)cp + k, u32x2{cw[(2 * k) < W ? 2 * k : 0], cw[(2 * k + 1) < W ? 2 * k + 1 : 0]});
-            } else {
-#pragma unroll
-                for (int k = 0; k < W; ++k) st<NTS>(cp + k, cw[k]);
-            }
-            if (sf.sbits == 8) {
-                uint8_t *sp = (uint8_t *)a.scales_out + wave_chunk0 * NB + lane * NB;
-                if (NB == 1) *sp = (uint8_t)sbytes;
-                else if (NB == 2) *(uint16_t *)sp = (uint16_t)sbytes;
-                else *(uint32_t *)sp = sbytes;
-            }
-        }
-        if (sf.sbits < 8 && wave_chunk0 < nchunks) {
-            // packed scale stream: each lane contributes NB fields of s bits = one wider field
-            uint32_t field = 0;
-#pragma unroll
-            for (int n = 0; n < NB; ++n) field |= ((sbytes >> (8 * n)) & 0xFFu) << (n * sf.sbits);
-            const size_t left = nchunks - wave_chunk0;
-            store_packed_fields<1>((uint8_t *)a.scales_out + ((wave_chunk0 * NB * (size_t)sf.sbits) >> 3),
-                                   valid ? field : 0u, NB * sf.sbits, (int)(left < 64 ? left : 64));
-        }
-        return;
+    for (int k = 0; k < 4; ++k) {
+        const int g = k * 64 + lane;             // piece index within the wave's 4 KiB
+        pv[k] = (size_t)g < own_pieces ? ld<NTL>(src + g) : u32x4{0u, 0u, 0u, 0u};
     }
+}
 
-    // Exchange through LDS.  Lane l owns output pieces l*OC .. l*OC+OC-1 of the wave's tile; piece
-    // c is written to slot (c + l) % OC of the lane's row so that both the row-wise writes and
-    // the piece-wise reads spread over all banks.
-    u32x4 *t = tile[wave];
+__device__ __forceinline__ void take_raw_chunk(u32x4 *t, const u32x4 (&pv)[4], u32x4 (&own)[4], int lane)
+{
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int g = k * 64 + lane;
+        const int l = g >> 2, c = g & 3;         // owner lane and its piece number
+        t[l * 4 + ((c + l) & 3)] = pv[k];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int c = 0; c < 4; ++c) own[c] = t[lane * 4 + ((c + lane) & 3)];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Writes the wave tile's sums.  Exchange through LDS: lane l owns output pieces l*OC .. l*OC+OC-1
+// of the wave's tile; piece c is written to slot (c + l) % OC of the lane's row so that both the
+// row-wise writes and the piece-wise reads spread over all banks.  The wave then writes its
+// output as contiguous 1 KiB store instructions.
+template <bool OUT_BF16, bool NTS>
+__device__ __forceinline__ void store_sums(u32x4 *t, const float (&acc)[32], void *outp, size_t wave_chunk0,
+                                           int lane, size_t nchunks)
+{
+    constexpr int OC = OUT_BF16 ? 4 : 8;         // 16-byte output pieces per lane
 #pragma unroll
     for (int c = 0; c < OC; ++c) {
         u32x4 v;
@@ -1108,7 +1055,7 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    u32x4 *out = (u32x4 *)a.out + wave_chunk0 * OC;
+    u32x4 *out = (u32x4 *)outp + wave_chunk0 * OC;
     const size_t pieces_left = wave_chunk0 < nchunks ? (nchunks - wave_chunk0) * OC : 0;
 #pragma unroll
     for (int r = 0; r < OC; ++r) {
@@ -1117,6 +1064,316 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
         const u32x4 v = t[l * OC + ((c + l) & (OC - 1))];
         if ((size_t)g < pieces_left) st<NTS>(out + g, v);
     }
+}
+
+// Fused form: quantizes the lane's 32 sums again (same rule as the quantizer applied to binary32
+// input) and stores codes and scales.  The lane holds whole blocks, so block maximum, scale and
+// codes need no other lane.  Every lane of the wave must call this (narrow scales are gathered
+// across the wave).
+template <class E, int B, bool NTS, bool HW>
+__device__ __forceinline__ void requantize_sums(const float (&acc)[32], void *codes_out, void *scales_out,
+                                                size_t wave_chunk0, int lane, size_t nchunks,
+                                                const ScaleFmt &sf)
+{
+    constexpr int W = E::bits, NB = 32 / B;
+    constexpr bool kHw = HW && E::hw != HW_NONE;
+    constexpr bool kChunkBf6 = E::x == 3 && E::y == 2 && B == 32;
+    const bool valid = wave_chunk0 + (size_t)lane < nchunks;
+    uint32_t cw[W];
+#pragma unroll
+    for (int k = 0; k < W; ++k) cw[k] = 0u;
+    uint32_t sbytes = 0;
+#pragma unroll
+    for (int n = 0; n < NB; ++n) {
+        uint32_t m = 0;
+#pragma unroll
+        for (int j = 0; j < B; ++j) m = max(m, __float_as_uint(acc[n * B + j]) & 0x7FFFFFFFu);
+        const int expfield = (int)(m >> 23);
+        int sc = 0;
+        if (kHw && kChunkBf6) {
+            // one instruction rounds the lane's 32 sums to BF6 = E3M2 (same scale rule)
+            const int unclamped = expfield - 127 - E::emax + sf.sbias;
+            const bool finite = expfield != 255;
+            sc = finite ? min(max(unclamped, 0), sf.smax) : sf.nonfinite;
+            const int fld = sc - sf.sbias + 127;
+            if (__builtin_amdgcn_ballot_w64(finite && (fld < 0 || fld > 254)) == 0) {
+                // the instruction interleaves its two sources: result code 2j comes from the
+                // first operand's element j, code 2j+1 from the second operand's
+                f32x16 even, odd;
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    even[j] = acc[2 * j];
+                    odd[j] = acc[2 * j + 1];
+                }
+                // Issued as inline assembly with an early-clobber result: through the builtin the
+                // register allocator let the six result registers overlap the per-lane scale
+                // register, and every code after the first two came out wrong.
+                u32x6 q;
+                const float hs = __uint_as_float((uint32_t)max(fld, 0) << 23);
+                asm("v_cvt_scalef32_2xpk16_bf6_f32 %0, %1, %2, %3"
+                    : "=&v"(q)
+                    : "v"(even), "v"(odd), "v"(hs));
+#pragma unroll
+                for (int k = 0; k < W; ++k) cw[k] = finite ? q[k < 6 ? k : 0] : 0u;
+                sbytes |= (uint32_t)sc << (8 * n);
+                continue;
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < B / 8; ++g) {
+            const int first = n * B + g * 8;
+            u32x4 w2[2];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                w2[0][j] = __float_as_uint(acc[first + j]);
+                w2[1][j] = __float_as_uint(acc[first + 4 + j]);
+            }
+            const uint64_t packed = encode_unit<E, true, HW>(w2, expfield, sf, &sc);
+            // 8b bits at bit first*b of the chunk's stream (constant positions)
+            const int pos = first * W;
+            cw[pos >> 5] |= (uint32_t)(packed << (pos & 31));
+            if ((pos & 31) + 8 * W > 32) {
+                const uint64_t rest = packed >> (32 - (pos & 31));
+                cw[((pos >> 5) + 1) < W ? (pos >> 5) + 1 : 0] |= (uint32_t)rest;
+                if ((pos & 31) + 8 * W > 64)
+                    cw[((pos >> 5) + 2) < W ? (pos >> 5) + 2 : 0] |= (uint32_t)(rest >> 32);
+            }
+        }
+        sbytes |= (uint32_t)sc << (8 * n);
+    }
+    if (valid) {
+        uint32_t *cp = (uint32_t *)codes_out + wave_chunk0 * W + lane * W;
+        if (W == 4) {
+            st<NTS>((u32x4 *)cp, u32x4{cw[0], cw[1], cw[2], cw[3 < W ? 3 : 0]});
+        } else if (W == 6) {
+            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+            for (int k = 0; k < 3; ++k)
+                st<NTS>((u32x2 *)cp + k, u32x2{cw[(2 * k) < W ? 2 * k : 0], cw[(2 * k + 1) < W ? 2 * k + 1 : 0]});
+        } else {
+#pragma unroll
+            for (int k = 0; k < W; ++k) st<NTS>(cp + k, cw[k]);
+        }
+        if (sf.sbits == 8) {
+            uint8_t *sp = (uint8_t *)scales_out + wave_chunk0 * NB + lane * NB;
+            if (NB == 1) *sp = (uint8_t)sbytes;
+            else if (NB == 2) *(uint16_t *)sp = (uint16_t)sbytes;
+            else *(uint32_t *)sp = sbytes;
+        }
+    }
+    if (sf.sbits < 8 && wave_chunk0 < nchunks) {
+        // packed scale stream: each lane contributes NB fields of s bits = one wider field
+        uint32_t field = 0;
+#pragma unroll
+        for (int n = 0; n < NB; ++n) field |= ((sbytes >> (8 * n)) & 0xFFu) << (n * sf.sbits);
+        const size_t left = nchunks - wave_chunk0;
+        store_packed_fields<1>((uint8_t *)scales_out + ((wave_chunk0 * NB * (size_t)sf.sbits) >> 3),
+                               valid ? field : 0u, NB * sf.sbits, (int)(left < 64 ? left : 64));
+    }
+}
+
+// Loads the code dwords of RC ranks for a full wave tile (64 valid chunks) with contiguous
+// 128-bit loads: a rank's 64 chunks are 16*W pieces of 16 bytes, piece p going to lane p % 64, so
+// every load instruction covers whole cache lines (a lane's own W dwords are 4*W bytes apart,
+// and loading them directly touches each line with several instructions).  The pieces pass
+// through the wave's LDS area `t` (RC * 16 * W pieces), from which each lane reads its W dwords.
+// Rank r0 + i is loaded when `on[i]`; the others read as zero.  Not for W == 4, where a chunk is
+// one piece already.
+template <int W, int RC, bool NTL>
+__device__ __forceinline__ void load_codes_staged(uint32_t (&cw)[RC][W], u32x4 *t, const void *(&codes)[RC],
+                                                  const bool (&on)[RC], size_t wave_chunk0, int lane)
+{
+    constexpr int NP = 16 * W;                   // pieces per rank: 48, 80 or 96
+    constexpr int K = (NP + 63) / 64;            // load instructions per rank
+    u32x4 pv[RC][K];
+#pragma unroll
+    for (int i = 0; i < RC; ++i) {
+        const u32x4 *src = (const u32x4 *)((const uint32_t *)codes[i] + wave_chunk0 * W);
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const int p = k * 64 + lane;
+            pv[i][k] = (on[i] && p < NP) ? ld<NTL>(src + p) : u32x4{0u, 0u, 0u, 0u};
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < RC; ++i)
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const int p = k * 64 + lane;
+            if (p < NP) t[i * NP + p] = pv[i][k];
+        }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const uint32_t *tw = (const uint32_t *)t;
+#pragma unroll
+    for (int i = 0; i < RC; ++i) {
+        if (W % 2 == 0) {
+            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+            for (int k = 0; k < W / 2; ++k) {
+                const u32x2 v = *(const u32x2 *)(tw + i * NP * 4 + lane * W + 2 * k);
+                cw[i][(2 * k) < W ? 2 * k : 0] = v.x;
+                cw[i][(2 * k + 1) < W ? 2 * k + 1 : 0] = v.y;
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < W; ++k) cw[i][k] = tw[i * NP * 4 + lane * W + k];
+        }
+    }
+    // the area is free again once every lane has read its dwords
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// The same redistribution with loads that write LDS directly (no registers in between): the
+// pieces of RC ranks are requested here; once the wave has waited for its vector-memory counter
+// to reach zero, read_codes_from_lds hands each lane its W dwords.
+template <int W, int RC, bool NTL>
+__device__ __forceinline__ void request_codes_to_lds(u32x4 *t, const void *(&codes)[RC], const bool (&on)[RC],
+                                                     size_t wave_chunk0, int lane)
+{
+    constexpr int NP = 16 * W;
+    constexpr int K = (NP + 63) / 64;
+    typedef const void __attribute__((address_space(1))) *gptr;
+    typedef void __attribute__((address_space(3))) *lptr;
+#pragma unroll
+    for (int i = 0; i < RC; ++i) {
+        const u32x4 *src = (const u32x4 *)((const uint32_t *)codes[i] + wave_chunk0 * W);
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const int p = k * 64 + lane;
+            // lane l's 16 bytes land at the given LDS address + 16 * l
+            if (on[i] && p < NP)
+                __builtin_amdgcn_global_load_lds((gptr)(src + p), (lptr)(t + i * NP + k * 64), 16, 0, NTL ? 2 : 0);
+        }
+    }
+}
+
+// Rank slot i of the area filled by request_codes_to_lds: the lane's W dwords.
+template <int W>
+__device__ __forceinline__ void read_codes_from_lds(uint32_t (&cw)[W], const u32x4 *t, int i, int lane)
+{
+    constexpr int NP = 16 * W;
+    const uint32_t *tw = (const uint32_t *)t + i * NP * 4 + lane * W;
+    if (W % 2 == 0) {
+        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+        for (int k = 0; k < W / 2; ++k) {
+            const u32x2 v = *(const u32x2 *)(tw + 2 * k);
+            cw[(2 * k) < W ? 2 * k : 0] = v.x;
+            cw[(2 * k + 1) < W ? 2 * k + 1 : 0] = v.y;
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < W; ++k) cw[k] = tw[k];
+    }
+}
+
+// The kernel: one wave per wave tile, no workgroup barrier.
+//
+// RC: ranks whose loads are issued together.  FUSED: instead of storing the sums, quantize them
+// again in the lane that holds them and store codes and scales; bit-identical to running the
+// unfused kernels one after the other.  OWN: rank a.own_rank contributes its uncompressed bf16
+// partial.  STAGED: 3-, 5- and 6-bit codes are loaded as contiguous 16-byte pieces and
+// redistributed through LDS (load_codes_staged).  WG: threads per workgroup (a multiple of 64).
+template <class E, int B, bool OUT_BF16, int RC, bool NTL, bool NTS, bool HW, bool FUSED = false,
+          bool OWN = false, int WG = kThreads, int STAGE = 0>
+__global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
+{
+    static_assert(!(FUSED && OWN), "the fused form has no own-raw variant");
+    constexpr int NB = 32 / B;                   // blocks (scales) per chunk
+    constexpr int W = E::bits;                   // dwords of codes per chunk
+    constexpr int OC = OUT_BF16 ? 4 : 8;         // 16-byte output pieces per lane
+    constexpr bool kStaged = STAGE != 0 && W != 4;
+    constexpr bool kDma = kStaged && STAGE == 2;
+    // LDS per wave, in 16-byte pieces: the output exchange, the staging of code pieces and the
+    // own rank's raw pieces use the same area one after the other
+    constexpr int kOutPieces = FUSED ? 0 : 64 * OC;
+    constexpr int kStagePieces = kStaged ? RC * 16 * W : 0;
+    constexpr int kOwnPieces = OWN ? 256 : 0;
+    constexpr int kPieces = kOutPieces > kStagePieces ? (kOutPieces > kOwnPieces ? kOutPieces : kOwnPieces)
+                                                      : (kStagePieces > kOwnPieces ? kStagePieces : kOwnPieces);
+    __shared__ u32x4 tile[WG / 64][kPieces > 0 ? kPieces : 1];
+
+    const int lane = (int)(threadIdx.x & 63);
+    // the wave index is the same in every lane: telling the compiler so keeps wave_chunk0 and
+    // every base address derived from it in scalar registers, and the per-lane part of an
+    // address a 32-bit offset
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const size_t wave_chunk0 = ((size_t)blockIdx.x * (WG / 64) + (size_t)wave) * 64;
+    const size_t nchunks = a.units / 4;
+    if (wave_chunk0 >= nchunks) return;          // the whole wave
+    const bool valid = wave_chunk0 + (size_t)lane < nchunks;
+    const bool full = wave_chunk0 + 64 <= nchunks;
+    const ScaleFmt sf = a.sf;
+    u32x4 *t = tile[kPieces > 0 ? wave : 0];
+
+    float acc[32];
+#pragma unroll
+    for (int j = 0; j < 32; ++j) acc[j] = kFoldStart;
+    bool poisoned[NB];
+#pragma unroll
+    for (int n = 0; n < NB; ++n) poisoned[n] = false;
+
+    u32x4 own[4];
+    if constexpr (OWN) {
+        u32x4 pv[4];
+        load_raw_pieces<NTL>(pv, a.own_x, wave_chunk0, lane, nchunks);
+        take_raw_chunk(t, pv, own, lane);
+    }
+
+    for (int r0 = 0; r0 < a.tp; r0 += RC) {
+        ChunkBits<W> g[RC];
+        bool on[RC];
+        const void *cptr[RC];
+#pragma unroll
+        for (int i = 0; i < RC; ++i) {
+            const int r = r0 + i;
+            const int rr = min(r, a.tp - 1);
+            on[i] = r < a.tp && !(OWN && r == a.own_rank);
+            cptr[i] = a.codes[rr];
+            // with staged code loads this fetches the scales only
+            load_chunk<E, B, NTL, kStaged>(g[i], cptr[i], a.scales[rr], wave_chunk0, lane, valid && on[i], sf,
+                                           nchunks, full);
+        }
+        if (kStaged && !kDma && full) {
+            uint32_t cw[RC][W];
+            load_codes_staged<W, RC, NTL>(cw, t, cptr, on, wave_chunk0, lane);
+#pragma unroll
+            for (int i = 0; i < RC; ++i)
+#pragma unroll
+                for (int k = 0; k < W; ++k) g[i].cw[k] = cw[i][k];
+        }
+        if (kDma && full) {
+            request_codes_to_lds<W, RC, NTL>(t, cptr, on, wave_chunk0, lane);
+            __builtin_amdgcn_s_waitcnt(0);       // every counter at zero: the pieces are in LDS
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+#pragma unroll
+        for (int i = 0; i < RC; ++i) {
+            if (OWN && r0 + i == a.own_rank) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) add_raw_bf16(own[k], acc + 8 * k);
+            } else if (r0 + i < a.tp) {
+                // each rank's dwords are fetched from LDS only when its turn comes
+                if (kDma && full) read_codes_from_lds<W>(g[i].cw, t, i, lane);
+                add_chunk<E, B, HW>(g[i], sf, acc, poisoned);
+            }
+        }
+        if (kDma && full) {
+            // the area is free again once every lane has read its dwords
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+    apply_poison<B>(acc, poisoned);
+    if (FUSED)
+        requantize_sums<E, B, NTS, HW>(acc, a.codes_out, a.scales_out, wave_chunk0, lane, nchunks, sf);
+    else
+        store_sums<OUT_BF16, NTS>(t, acc, a.out, wave_chunk0, lane, nchunks);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -11,7 +11,9 @@ int reduce_requantize(const mxc_format *f, const ReduceArgs &a, hipStream_t st)
         constexpr int B = decltype(block)::value;
         const size_t chunks = a.units / 4;
         const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads));
-        return launch(dequant_reduce_tile_kernel<E, B, false, kFusedRC, kReduceNTL, kQuantNTS, kHw, true>,
+        constexpr TileShape ts = tile_shape(E::bits, false, true, false);
+        return launch(dequant_reduce_tile_kernel<E, B, false, ts.rc, kReduceNTL, kQuantNTS, kHw, true, false,
+                                                 kThreads, ts.stage>,
                       grid, st, a);
     });
 }
