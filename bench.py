@@ -12,12 +12,15 @@ packed buffers rotate over three sets (a step quantizes into one set and reduces
 was written two steps earlier), the bf16 inputs alternate between two copies and the reduced
 outputs rotate over four buffers.
 
-Prints ONE JSON line.  `roofline` is for the kernel that takes most of the step: achieved =
+Prints ONE JSON line.  `value` and `ms_per_step` are wall-clock over the K timed steps, which
+carry no instrumentation.  `roofline` is for the kernel that takes most of the step: achieved =
 algorithmic bytes per launch / average kernel duration, against the 8 TB/s HBM peak.  The
-duration comes from HIP events that the launch itself stamps at the kernel's begin and end
-(mxc_time_next_launch) on every fourth step of the timed region: a launch carrying events costs
-a few microseconds more than a plain one, which would otherwise show up in ms_per_step. 
-`cpu_baseline` is the CPU oracle timed on the same workload, for context.
+durations come from an instrumented pass right after the timed region: the same steps again,
+every launch stamping a pair of HIP events at the kernel's own begin and end
+(mxc_time_next_launch), at least 24 launches per kernel whatever --steps is.  `cpu_baseline` is
+the CPU oracle timed on the same workload, for context.  The untimed `sweep` adds the other
+element formats of the configuration, the other forms of the reduction, and the requantize
+pipelines of the two larger configurations, each kernel timed the same way.
 """
 from __future__ import annotations
 
@@ -33,7 +36,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-EVENT_EVERY = 4                # one step in this many has its two launches timed with HIP events
+MIN_TIMED_LAUNCHES = 24        # per kernel, in the instrumented pass and in the sweep
+QUANTIZE_KERNEL = "quantize_kernel"
+REDUCE_KERNEL = "dequant_reduce_tile_kernel"
 
 
 def parse_args():
@@ -45,7 +50,9 @@ def parse_args():
     ap.add_argument("--format", default="e2m1", help="element format of the timed step, e.g. e2m1")
     ap.add_argument("--ramp", type=float, default=0.15,
                     help="seconds of untimed load before the warm-up steps (clock conditioning)")
-    ap.add_argument("--no-sweep", action="store_true", help="skip the untimed format sweep")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the untimed sweep")
+    ap.add_argument("--no-pipelines", action="store_true",
+                    help="skip the requantize pipelines of configurations 4 and 5 in the sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--quality-table", action="store_true",
                     help="add the quality proxy (SQNR of the reduced output) for every element "
@@ -59,10 +66,16 @@ def parse_format(s):
     return int(s[1]), int(s[3])
 
 
-def algorithmic_bytes(fmt, tp, tokens, hidden):
-    """Bytes the method itself must move, per launch: (quantize, dequant-reduce)."""
+def packed_bytes(fmt, tokens, hidden):
+    """Code bytes + scale bytes of one [tokens x hidden] tensor (8-bit scales)."""
     n = tokens * hidden
-    packed = n * fmt.bits / 8 + n * 1 / fmt.block          # codes + one scale byte per block
+    return n * fmt.bits / 8 + n / fmt.block
+
+
+def algorithmic_bytes(fmt, tp, tokens, hidden):
+    """Bytes the method itself must move, per launch: (quantize, dequant-reduce to float32)."""
+    n = tokens * hidden
+    packed = packed_bytes(fmt, tokens, hidden)
     return tp * (n * 2 + packed), tp * packed + n * 4
 
 
@@ -113,6 +126,11 @@ def cpu_baseline(w, x, y, host_parts, rows, reps=3):
     }
 
 
+def sqnr_db(torch, out, exact):
+    err = (out.double() - exact.double()).pow(2).sum()
+    return 10.0 * float(torch.log10(exact.double().pow(2).sum() / err)) if float(err) > 0 else float("inf")
+
+
 def quality_table(mxc, torch, xs, T, H):
     """Quality proxy over the paper's whole parameter list (Method: element type, block size,
     scale type): SQNR in dB of the compressed TP reduction against the uncompressed sum of the
@@ -122,7 +140,6 @@ def quality_table(mxc, torch, xs, T, H):
     exact = xs[0].float()
     for t in xs[1:]:
         exact += t.float()
-    power = float(exact.double().pow(2).sum())
     out = torch.empty((T, H), dtype=torch.float32, device="cuda")
     table = {}
     elements = [(1, 1), (1, 2), (2, 1), (1, 3), (2, 2), (3, 1), (1, 4), (2, 3), (3, 2)]
@@ -132,12 +149,134 @@ def quality_table(mxc, torch, xs, T, H):
                 f = mxc.Format(fx, fy, fb, fs)
                 codes, scales = mxc.quantize_batched(f, xs)
                 mxc.dequant_reduce(f, codes, scales, T, H, out=out)
-                err = float((out - exact).double().pow(2).sum())
                 table[f"e{fx}m{fy}_b{fb}_s{fs}"] = {
-                    "effective_bits": mxc.effective_bits(f),
-                    "sqnr_db": 10.0 * float(np.log10(power / err)) if err > 0 else float("inf")}
+                    "effective_bits": mxc.effective_bits(f), "sqnr_db": sqnr_db(torch, out, exact)}
                 del codes, scales
     return table
+
+
+class KernelTimer:
+    """Durations of single kernels from HIP events that the launches stamp themselves."""
+
+    def __init__(self, mxc, torch):
+        self.mxc, self.torch = mxc, torch
+
+    def events(self, n):
+        ev = [(self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True))
+              for _ in range(n)]
+        stream = self.torch.cuda.current_stream()
+        for a, b in ev:
+            a.record(stream)                # creates the HIP event; the launch re-stamps it
+            b.record(stream)
+        return ev
+
+    def each(self, launch, n=MIN_TIMED_LAUNCHES, warm=30):
+        """launch(i) enqueues exactly one kernel: its duration in ms for i = 0..n-1."""
+        for i in range(warm):
+            launch(i)
+        ev = self.events(n)
+        self.torch.cuda.synchronize()
+        for i, (a, b) in enumerate(ev):
+            self.mxc.time_next_launch(a, b)
+            launch(i)
+        self.torch.cuda.synchronize()
+        return [a.elapsed_time(b) for a, b in ev]
+
+    def group(self, launches, n=MIN_TIMED_LAUNCHES, warm=10):
+        """`launches(i)` returns the list of one-kernel callables of repetition i: the sum of
+        their kernel durations in ms per repetition."""
+        for i in range(warm):
+            for l in launches(i):
+                l()
+        k = len(launches(0))
+        ev = self.events(n * k)
+        self.torch.cuda.synchronize()
+        for i in range(n):
+            for j, l in enumerate(launches(i)):
+                self.mxc.time_next_launch(*ev[i * k + j])
+                l()
+        self.torch.cuda.synchronize()
+        return [sum(ev[i * k + j][0].elapsed_time(ev[i * k + j][1]) for j in range(k)) for i in range(n)]
+
+
+def rate(nbytes, samples_ms):
+    ms = float(np.mean(samples_ms))
+    gbs = nbytes / ms / 1e6
+    return {"ms": ms, "hbm_GBps": gbs, "frac": gbs / HBM_PEAK_GBS, "launches_timed": len(samples_ms)}
+
+
+def device_partials(w, torch):
+    """The workload's recipe (workloads.py) drawn on the device with torch's generator: the same
+    channel profile, body values from a different random stream.  For timing only; the parity
+    tests use the numpy draws."""
+    import workloads
+    chan_scale, _, mult = workloads.channel_profile(w)
+    prof = torch.from_numpy(chan_scale * mult).cuda()
+    xs = []
+    for r in range(w.tp):
+        g = torch.Generator(device="cuda")
+        g.manual_seed(w.seed * 1000 + r + 1)
+        body = torch.randn((w.tokens, w.hidden), generator=g, device="cuda", dtype=torch.float32)
+        if w.body == "student_t3":
+            chi = torch.zeros_like(body)
+            for _ in range(3):
+                chi += torch.randn((w.tokens, w.hidden), generator=g, device="cuda").pow_(2)
+            body /= (chi / 3.0).sqrt_()
+            del chi
+        body *= prof[None, :]
+        xs.append(body.to(torch.bfloat16))
+        del body
+    return xs
+
+
+def pipeline_block(mxc, torch, timer, w, fmt_tuple):
+    """Quantize -> dequant-reduce -> requantize at one of the larger configurations, each kernel
+    timed by its own events: the unfused path (reduce the whole tensor to float32, requantize each
+    1/N row chunk) and the fused path (one launch per chunk: N compressed chunk copies in, one
+    compressed chunk out)."""
+    T, H, N = w.tokens, w.hidden, w.tp
+    f = mxc.Format(*fmt_tuple)
+    xs = device_partials(w, torch)
+    cb, sb = mxc.packed_sizes(f, T, H)
+    R = 2 if N * (cb + sb) > (256 << 20) else 3      # sets whose total exceeds the last-level cache
+    sets = []
+    for _ in range(R):
+        buf = torch.empty(N * (cb + sb), dtype=torch.uint8, device="cuda")
+        sets.append(([buf[r * (cb + sb): r * (cb + sb) + cb].view(T, cb // T) for r in range(N)],
+                     [buf[r * (cb + sb) + cb: (r + 1) * (cb + sb)].view(T, sb // T) for r in range(N)]))
+    outs = [torch.empty((T, H), dtype=torch.float32, device="cuda") for _ in range(2)]
+    ql = [mxc.prepare_quantize_batched(f, xs, *sets[k]) for k in range(R)]
+    dl = [mxc.prepare_dequant_reduce(f, *sets[k], T, H, outs[k % 2]) for k in range(R)]
+    for l in ql:
+        l()
+    n = T * H
+    packed = packed_bytes(f, T, H)
+    rows = T // N
+    ccb, csb = mxc.packed_sizes(f, rows, H)
+    cc = [torch.empty(ccb, dtype=torch.uint8, device="cuda") for _ in range(N)]
+    cs = [torch.empty(csb, dtype=torch.uint8, device="cuda") for _ in range(N)]
+    rq = [[mxc.prepare_requantize_chunk(f, outs[k], N, c, cc[c], cs[c]) for c in range(N)]
+          for k in range(2)]
+    fu = [[mxc.prepare_dequant_reduce_requantize(
+               f, [t[c * rows:(c + 1) * rows] for t in sets[k][0]],
+               [t[c * rows:(c + 1) * rows] for t in sets[k][1]], rows, H, cc[c], cs[c])
+           for c in range(N)] for k in range(R)]
+    q = rate(N * (n * 2 + packed), timer.each(lambda i: ql[i % R]()))
+    d = rate(N * packed + n * 4, timer.each(lambda i: dl[i % R]()))
+    r = rate(n * 4 + packed, timer.group(lambda i: rq[i % 2]))
+    fz = rate((N + 1) * packed, timer.group(lambda i: fu[i % R]))
+    block = {
+        "workload": w.name, "element": f"e{f.ebits}m{f.mbits}", "block": f.block,
+        "data": "synthetic, drawn on the device (same recipe, torch generator)",
+        "quantize": q, "dequant_reduce_f32": d,
+        "requantize_%d_chunks" % N: r,
+        "fused_reduce_requantize_%d_chunks" % N: fz,
+        "pipeline_unfused_ms": q["ms"] + d["ms"] + r["ms"],
+        "pipeline_fused_ms": q["ms"] + fz["ms"],
+    }
+    del xs, sets, outs, ql, dl, rq, fu
+    torch.cuda.empty_cache()
+    return block
 
 
 def main():
@@ -160,7 +299,7 @@ def main():
     x, y = parse_format(args.format)
     fmt = mxc.Format(x, y, 32, 8)
     T, H, N = w.tokens, w.hidden, w.tp
-    stream = torch.cuda.current_stream()
+    timer = KernelTimer(mxc, torch)
 
     # ---- inputs, resident in HBM -----------------------------------------------------------
     host_parts = workloads.all_partials_bf16(w)
@@ -194,9 +333,9 @@ def main():
     def step(i, ev=None):
         # the events are stamped by the two dispatches themselves (begin and end of each kernel),
         # so timing them puts nothing extra on the stream
-        if ev: mxc.time_next_launch(ev[0], ev[1])
+        if ev: mxc.time_next_launch(ev[0][0], ev[0][1])
         q_launch[i % PERIOD]()
-        if ev: mxc.time_next_launch(ev[2], ev[3])
+        if ev: mxc.time_next_launch(ev[1][0], ev[1][1])
         d_launch[i % PERIOD]()
 
     for i in range(R):                      # fill every packed set before anything is reduced
@@ -212,23 +351,23 @@ def main():
         step(i)
     torch.cuda.synchronize()
 
-    # ---- timed region ----------------------------------------------------------------------
-    # A launch that carries events costs about 5 us more than a plain one, so only every
-    # EVENT_EVERY-th step of the timed region is instrumented; all steps count for ms_per_step.
-    timed_steps = range(0, args.steps, EVENT_EVERY)
-    events = {i: [torch.cuda.Event(enable_timing=True) for _ in range(4)] for i in timed_steps}
-    for ev in events.values():
-        for e in ev:
-            e.record(stream)                # creates the HIP event; the launch re-stamps it
-    torch.cuda.synchronize()
+    # ---- timed region: K plain steps -------------------------------------------------------
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(i, events.get(i))
+        step(i)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    q_all = [e[0].elapsed_time(e[1]) for e in events.values()]
-    r_all = [e[2].elapsed_time(e[3]) for e in events.values()]
+
+    # ---- instrumented pass: the same steps, every launch carrying its pair of events -------
+    n_inst = max(MIN_TIMED_LAUNCHES, min(args.steps, 96))
+    events = [(timer.events(1)[0], timer.events(1)[0]) for _ in range(n_inst)]
+    torch.cuda.synchronize()
+    for i in range(n_inst):
+        step(args.steps + i, events[i])
+    torch.cuda.synchronize()
+    q_all = [e[0][0].elapsed_time(e[0][1]) for e in events]
+    r_all = [e[1][0].elapsed_time(e[1][1]) for e in events]
     q_ms, r_ms = float(np.mean(q_all)), float(np.mean(r_all))
 
     bf16_bytes = N * T * H * 2
@@ -242,17 +381,18 @@ def main():
         return {"kernel": kernel, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
                 "traffic": read_traffic(w.name, kernel, fname),
+                "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/hbm_traffic.txt",
                 "algorithmic_bytes_per_launch": nbytes, "avg_launch_ms": ms,
                 "median_launch_ms": float(np.median(samples)),
                 "min_launch_ms": float(np.min(samples)), "launches_timed": len(samples)}
 
-    rq, rr = roof("quantize_kernel", q_bytes, q_all), roof("dequant_reduce_kernel", r_bytes, r_all)
+    rq, rr = roof(QUANTIZE_KERNEL, q_bytes, q_all), roof(REDUCE_KERNEL, r_bytes, r_all)
     dominant = rq if q_ms >= r_ms else rr
 
     result = {
         # `value` is the whole step (quantize + dequant-reduce); the two kernels' own rates and
         # fractions of the HBM peak are under "kernels"
-        "metric": "quantize / dequant-reduce GB/s (bf16 in) and % of HBM peak, 1\u00d7 MI355X",
+        "metric": "quantize / dequant-reduce GB/s (bf16 in) and % of HBM peak, 1× MI355X",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16 in, u8 codes, f32 accumulate", "data": "synthetic",
@@ -266,106 +406,25 @@ def main():
         },
     }
 
-    # ---- untimed extras: copy ceiling and the other element formats of the configuration ----
+    # ---- untimed extras --------------------------------------------------------------------
     if not args.no_sweep:
-        def time_calls(fn, n=50, warm=100):
-            for i in range(warm):
-                fn(i)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            torch.cuda.synchronize()
-            e0.record(stream)
-            for i in range(n):
-                fn(i)
-            e1.record(stream)
-            torch.cuda.synchronize()
-            return e0.elapsed_time(e1) / n
         src = [torch.empty(512 << 20, dtype=torch.uint8, device="cuda") for _ in range(2)]
         dst = [torch.empty(512 << 20, dtype=torch.uint8, device="cuda") for _ in range(2)]
         for s in src:
             s.zero_()
-        cms = time_calls(lambda i: mxc.copy_probe(dst[i % 2], src[i % 2]))
-        copy_gbs = 2 * (512 << 20) / (cms * 1e-3) / 1e9
-        result["copy_ceiling"] = {"GBps": copy_gbs, "frac_of_peak": copy_gbs / HBM_PEAK_GBS,
-                                  "bytes_moved": 2 * (512 << 20)}
+        c = rate(2 * (512 << 20), timer.each(lambda i: mxc.copy_probe(dst[i % 2], src[i % 2])))
+        copy_gbs = c["hbm_GBps"]
+        result["copy_ceiling"] = {"kernel": "copy_kernel", "GBps": copy_gbs, "frac_of_peak": c["frac"],
+                                  "bytes_moved": 2 * (512 << 20), "launches_timed": c["launches_timed"]}
         for k in result["kernels"].values():
             k["frac_of_copy_ceiling"] = k["achieved"] / copy_gbs
         del src, dst
         sweep = {}
-        for (fx, fy, fb, fs) in w.formats:
-            f = mxc.Format(fx, fy, fb, fs)
-            ps = [packed_set(f) for _ in range(R)]
-            for i in range(R):
-                mxc.quantize_batched(f, x_sets[0], *ps[i])
-            qb, rb = algorithmic_bytes(f, N, T, H)
-            ql, dl = make_launches(f, ps)
-            qms = time_calls(lambda i: ql[i % PERIOD]())
-            rms = time_calls(lambda i: dl[i % PERIOD]())
-            # quality proxy on the synthetic tensors (the paper's perplexity tables need models
-            # and data): error of the reduced output against the uncompressed sum, plain torch
-            dl[0]()
-            exact = x_sets[0][0].float()
-            for r in range(1, N):
-                exact += x_sets[0][r].float()
-            err = (outs[0] - exact).double()
-            sqnr = 10.0 * float(torch.log10(exact.double().pow(2).sum() / err.pow(2).sum()))
-            del exact, err
-            sweep[f"e{fx}m{fy}_b{fb}"] = {
-                "compression_ratio": 16 / mxc.effective_bits(f),
-                "reduced_output_sqnr_db": sqnr,
-                "quantize": {"ms": qms, "GBps_bf16": bf16_bytes / qms / 1e6,
-                             "hbm_GBps": qb / qms / 1e6, "frac": qb / qms / 1e6 / HBM_PEAK_GBS,
-                             "frac_of_copy": qb / qms / 1e6 / copy_gbs},
-                "dequant_reduce": {"ms": rms, "GBps_bf16": bf16_bytes / rms / 1e6,
-                                   "hbm_GBps": rb / rms / 1e6, "frac": rb / rms / 1e6 / HBM_PEAK_GBS,
-                                   "frac_of_copy": rb / rms / 1e6 / copy_gbs},
-            }
-            del ps
-        # requantize (extension): every 1/N row chunk of the reduced tensor, one launch per chunk
-        # as the ranks would issue them, and the whole tensor in one launch (tp = 1) to show the
-        # kernel's streaming rate without the launch gaps
-        f = mxc.Format(*w.formats[-1])
-        red = outs[0]
-        cb, sb = mxc.packed_sizes(f, T // N, H)
-        cc = [torch.empty(cb, dtype=torch.uint8, device="cuda") for _ in range(N)]
-        sc = [torch.empty(sb, dtype=torch.uint8, device="cuda") for _ in range(N)]
-        rl = [mxc.prepare_requantize_chunk(f, red, N, c, cc[c], sc[c]) for c in range(N)]
-        def requant_all(i):
-            for l in rl:
-                l()
-        ms = time_calls(requant_all)
-        nb = T * H * 4 + N * (cb + sb)
-        sweep["requantize_%d_chunks_%d_launches" % (N, N)] = {
-            "ms": ms, "hbm_GBps": nb / ms / 1e6, "frac": nb / ms / 1e6 / HBM_PEAK_GBS}
-        cbw, sbw = mxc.packed_sizes(f, T, H)
-        reds = outs[:3]
-        cw = [torch.empty(cbw, dtype=torch.uint8, device="cuda") for _ in range(3)]
-        sw = [torch.empty(sbw, dtype=torch.uint8, device="cuda") for _ in range(3)]
-        wl = [mxc.prepare_requantize_chunk(f, reds[k], 1, 0, cw[k], sw[k]) for k in range(3)]
-        ms = time_calls(lambda i: wl[i % 3]())
-        sweep["requantize_whole_tensor_f32"] = {
-            "ms": ms, "hbm_GBps": nb / ms / 1e6, "frac": nb / ms / 1e6 / HBM_PEAK_GBS}
-        # fused dequant-reduce + requantize of one rank's chunk (N compressed chunk copies in, one
-        # compressed chunk out), and of the whole tensor in one launch to show the streaming rate
-        fsets = [packed_set(f) for _ in range(R)]
-        for i in range(R):
-            mxc.quantize_batched(f, x_sets[0], *fsets[i])
-        n_rows = T // N
-        fl = [mxc.prepare_dequant_reduce_requantize(
-                  f, [c[:n_rows] for c in fsets[k][0]], [s_[:n_rows] for s_ in fsets[k][1]],
-                  n_rows, H, cc[0], sc[0]) for k in range(R)]
-        ms = time_calls(lambda i: fl[i % R]())
-        nbf = N * (cb + sb) + cb + sb
-        sweep["fused_reduce_requantize_one_chunk"] = {
-            "ms": ms, "hbm_GBps": nbf / ms / 1e6, "frac": nbf / ms / 1e6 / HBM_PEAK_GBS}
-        fw = [mxc.prepare_dequant_reduce_requantize(f, fsets[k][0], fsets[k][1], T, H, cw[k], sw[k])
-              for k in range(R)]
-        ms = time_calls(lambda i: fw[i % R]())
-        nbw = N * (cbw + sbw) + cbw + sbw
-        sweep["fused_reduce_requantize_whole_tensor"] = {
-            "ms": ms, "hbm_GBps": nbw / ms / 1e6, "frac": nbw / ms / 1e6 / HBM_PEAK_GBS}
-        # the reduction as the paper's Profiling section words it: the worker's own partial raw,
-        # the other N-1 decoded, bf16 out (the dtype the next layer consumes); and the
-        # rank-consistent all-decoded form with bf16 out
+        # the element formats of the configuration: both kernels, the quality proxy, and the
+        # other forms of the reduction (bf16 out; the paper's own-partial-raw form with bf16 out)
+        exact = x_sets[0][0].float()
+        for r in range(1, N):
+            exact += x_sets[0][r].float()
         # eight bf16 outputs (the two halves of each float32 buffer) keep the rotation at 512 MiB
         outs16 = [o.view(-1).view(torch.bfloat16)[h * T * H:(h + 1) * T * H].view(T, H)
                   for o in outs for h in (0, 1)]
@@ -375,23 +434,59 @@ def main():
             ps = [packed_set(f) for _ in range(R)]
             for i in range(R):
                 mxc.quantize_batched(f, x_sets[0], *ps[i])
-            cbk, sbk = mxc.packed_sizes(f, T, H)
+            qb, rb = algorithmic_bytes(f, N, T, H)
+            pk = packed_bytes(f, T, H)
+            ql, dl = make_launches(f, ps)
+            entry = {"compression_ratio": 16 / mxc.effective_bits(f)}
+            entry["quantize"] = {"kernel": QUANTIZE_KERNEL, **rate(qb, timer.each(lambda i: ql[i % PERIOD]()))}
+            entry["dequant_reduce"] = {"kernel": REDUCE_KERNEL, **rate(rb, timer.each(lambda i: dl[i % PERIOD]()))}
+            for k in ("quantize", "dequant_reduce"):
+                entry[k]["GBps_bf16"] = bf16_bytes / entry[k]["ms"] / 1e6
+                entry[k]["frac_of_copy"] = entry[k]["hbm_GBps"] / copy_gbs
+            # quality proxy on the synthetic tensors (the paper's perplexity tables need models
+            # and data): error of the reduced output against the uncompressed sum, plain torch
+            dl[0]()
+            entry["reduced_output_sqnr_db"] = sqnr_db(torch, outs[0], exact)
             dl16 = [mxc.prepare_dequant_reduce(f, *ps[i % R], T, H, outs16[i % NOUT16])
                     for i in range(2 * PERIOD)]
-            ms = time_calls(lambda i: dl16[i % (2 * PERIOD)]())
-            nb16 = N * (cbk + sbk) + T * H * 2
-            sweep[f"dequant_reduce_bf16_out_e{fx}m{fy}"] = {
-                "ms": ms, "hbm_GBps": nb16 / ms / 1e6, "frac": nb16 / ms / 1e6 / HBM_PEAK_GBS}
-            ms = time_calls(lambda i: mxc.dequant_reduce_own(
-                f, i % N, x_sets[i % 2][i % N], ps[i % R][0], ps[i % R][1], out=outs16[i % NOUT16]))
-            nbo = (N - 1) * (cbk + sbk) + T * H * 2 + T * H * 2
-            sweep[f"dequant_reduce_own_raw_bf16_out_e{fx}m{fy}"] = {
-                "ms": ms, "hbm_GBps": nbo / ms / 1e6, "frac": nbo / ms / 1e6 / HBM_PEAK_GBS}
-            del ps, dl16
+            entry["dequant_reduce_bf16_out"] = rate(
+                N * pk + T * H * 2, timer.each(lambda i: dl16[i % (2 * PERIOD)]()))
+            entry["dequant_reduce_own_raw_bf16_out"] = rate(
+                (N - 1) * pk + T * H * 2 + T * H * 2,
+                timer.each(lambda i: mxc.dequant_reduce_own(
+                    f, i % N, x_sets[i % 2][i % N], ps[i % R][0], ps[i % R][1],
+                    out=outs16[i % NOUT16])))
+            # requantize (extension): every 1/N row chunk of the reduced tensor, one launch per
+            # chunk as the ranks would issue them, and the whole tensor in one launch
+            rows = T // N
+            ccb, csb = mxc.packed_sizes(f, rows, H)
+            cc = [torch.empty(ccb, dtype=torch.uint8, device="cuda") for _ in range(N)]
+            sc = [torch.empty(csb, dtype=torch.uint8, device="cuda") for _ in range(N)]
+            rl = [[mxc.prepare_requantize_chunk(f, outs[k], N, c_, cc[c_], sc[c_]) for c_ in range(N)]
+                  for k in range(NOUT)]
+            entry["requantize_%d_chunks" % N] = rate(T * H * 4 + pk, timer.group(lambda i: rl[i % NOUT]))
+            cbw, sbw = mxc.packed_sizes(f, T, H)
+            cw = [torch.empty(cbw, dtype=torch.uint8, device="cuda") for _ in range(3)]
+            sw = [torch.empty(sbw, dtype=torch.uint8, device="cuda") for _ in range(3)]
+            wl = [mxc.prepare_requantize_chunk(f, outs[k], 1, 0, cw[k % 3], sw[k % 3]) for k in range(NOUT)]
+            entry["requantize_whole_tensor_f32"] = rate(T * H * 4 + pk, timer.each(lambda i: wl[i % NOUT]()))
+            # fused dequant-reduce + requantize: the N chunks one launch each, and the whole
+            # tensor in one launch to show the streaming rate
+            fl = [[mxc.prepare_dequant_reduce_requantize(
+                       f, [t[c_ * rows:(c_ + 1) * rows] for t in ps[k][0]],
+                       [t[c_ * rows:(c_ + 1) * rows] for t in ps[k][1]], rows, H, cc[c_], sc[c_])
+                   for c_ in range(N)] for k in range(R)]
+            entry["fused_reduce_requantize_%d_chunks" % N] = rate((N + 1) * pk, timer.group(lambda i: fl[i % R]))
+            fw = [mxc.prepare_dequant_reduce_requantize(f, ps[k][0], ps[k][1], T, H, cw[k], sw[k])
+                  for k in range(R)]
+            entry["fused_reduce_requantize_whole_tensor"] = rate((N + 1) * pk, timer.each(lambda i: fw[i % R]()))
+            sweep[f"e{fx}m{fy}_b{fb}"] = entry
+            del ps, ql, dl, dl16, rl, wl, fl, fw, cc, sc, cw, sw
+        del exact
         # the paper's own profiled input sizes are a few hundred tokens (Table 3: 2x64 ... 16x256):
         # one rank's quantize and the N-way reduce at 256 tokens, where a call is launch-bound
         f = mxc.Format(2, 1, 32, 8)
-        Ts = 256
+        Ts = min(256, T)
         xs_small = [x_sets[0][r][:Ts] for r in range(N)]
         cbs, sbs = mxc.packed_sizes(f, Ts, H)
         cs_small = [torch.empty((Ts, cbs // Ts), dtype=torch.uint8, device="cuda") for _ in range(N)]
@@ -401,21 +496,35 @@ def main():
         qn = mxc.prepare_quantize_batched(f, xs_small, cs_small, ss_small)
         rn = mxc.prepare_dequant_reduce(f, cs_small, ss_small, Ts, H, out_small)
         qn()
-        def small_step(i):
+        stream = torch.cuda.current_stream()
+        def wall_us(fn, n=50, warm=100):
+            for i in range(warm):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record(stream)
+            for i in range(n):
+                fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n * 1e3
+        def small_step():
             qn()
             rn()
-        eager_us = time_calls(small_step) * 1e3
+        eager_us = wall_us(small_step)
         # the same step recorded once into a HIP graph and replayed (the library never allocates
         # or synchronises, so its calls can be captured)
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             for _ in range(10):
-                small_step(0)
-        graph_us = time_calls(lambda i: graph.replay(), n=20, warm=20) * 1e3 / 10
-        sweep["paper_sized_256_tokens_e2m1"] = {
-            "quantize_one_partial_us": time_calls(lambda i: q1()) * 1e3,
-            "dequant_reduce_%d_partials_us" % N: time_calls(lambda i: rn()) * 1e3,
+                small_step()
+        graph_us = wall_us(graph.replay, n=20, warm=20) / 10
+        sweep["paper_sized_%d_tokens_e2m1" % Ts] = {
+            "quantize_one_partial_kernel_us": float(np.mean(timer.each(lambda i: q1()))) * 1e3,
+            "dequant_reduce_%d_partials_kernel_us" % N: float(np.mean(timer.each(lambda i: rn()))) * 1e3,
+            "quantize_one_partial_call_us": wall_us(q1),
+            "dequant_reduce_%d_partials_call_us" % N: wall_us(rn),
             "step_quantize_%d_plus_reduce_eager_us" % N: eager_us,
             "step_quantize_%d_plus_reduce_graph_replay_us" % N: graph_us,
         }
@@ -423,6 +532,16 @@ def main():
 
     if args.quality_table:
         result["quality_table"] = quality_table(mxc, torch, x_sets[0], T, H)
+
+    # ---- the requantize pipelines of the two larger configurations (default workload only) --
+    if not args.no_sweep and not args.no_pipelines and args.config == 3:
+        del x_sets, sets, outs, q_launch, d_launch
+        torch.cuda.empty_cache()
+        result["pipelines"] = {
+            "config4_b16": pipeline_block(mxc, torch, timer, workloads.CONFIGS[4], workloads.CONFIGS[4].formats[0]),
+            "config4_b32": pipeline_block(mxc, torch, timer, workloads.CONFIGS[4], workloads.CONFIGS[4].formats[1]),
+            "config5": pipeline_block(mxc, torch, timer, workloads.CONFIGS[5], workloads.CONFIGS[5].formats[0]),
+        }
 
     if not args.no_cpu_baseline:
         rows = args.cpu_rows or min(T, 4096)
