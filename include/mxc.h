@@ -13,32 +13,45 @@
  * has the all-gather form.
  *
  * Common rules
- *   - Tensors are row-major [tokens x hidden]; blocks are `block` consecutive elements of one
- *     row, so hidden % block == 0 is required.
- *   - Element format ExMy: sign-magnitude, b = 1 + ebits + mbits bits, code =
- *     sign << (x+y) | exp << y | mant, exponent bias 2^(x-1)-1, no Inf/NaN codes, exp == 0 is
- *     subnormal.  Scale EsM0: per block the code e + (2^(s-1)-1), the block's values being
- *     code_value * 2^e.  For s = 8 the code 255 marks a block that held an Inf/NaN.
- *   - Shared exponent e = floor(log2(max|v|)) - emax clamped to the scale's range; elements are
- *     rounded to the nearest magnitude, ties to the even code, saturating at the largest
- *     magnitude; the sign bit is the input's sign bit.  A block containing Inf/NaN stores
- *     all-zero codes and scale byte 255 (s = 8) or the largest scale code (s < 8).
- *   - Packed codes: element j of a row occupies bits [j*b, (j+1)*b) of the row's little-endian
- *     bit stream, rows back to back (hidden*b/8 bytes each).  Scales, s = 8: uint8 [tokens x
- *     hidden/block], row-major.  Scales, s < 8: a bit stream over all blocks of the tensor in
- *     the same order, block k at bits [k*s, (k+1)*s), LSB first, ceil(blocks*s/8) bytes, unused
- *     bits of the last byte zero.
- *   - Every data pointer is a DEVICE pointer owned by the caller, valid until the stream has
- *     finished the call.  Arrays of pointers (`const void* const*`) are HOST arrays of device
- *     pointers; they are read during the call and need not outlive it.
- *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Each call
- *     validates its arguments on the host, enqueues its kernel(s) on that stream and returns
- *     without synchronising.  The library allocates nothing and keeps no state (other than the
- *     pair of events mxc_time_next_launch arms for one launch of the calling thread).
- *   - Return value: MXC_OK or a negative mxc_status.  On error nothing has been enqueued.
- *   - Alignment: bf16/f32 tensors and packed code arrays must be 16-byte aligned, scale arrays
- *     4-byte aligned (MXC_ERR_ALIGN otherwise).  A requantize chunk's rows start at multiples of
- *     tokens/tp rows, which keeps this alignment for every supported shape.
+ *   1. Tensors are row-major [tokens x hidden]; blocks are `block` consecutive elements of one
+ *      row, so hidden % block == 0 is required.
+ *   2. Element format ExMy: sign-magnitude, b = 1 + ebits + mbits bits, code =
+ *      sign << (x+y) | exp << y | mant, exponent bias 2^(x-1)-1, no Inf/NaN codes, exp == 0 is
+ *      subnormal.  Scale EsM0: per block the code e + (2^(s-1)-1), the block's values being
+ *      code_value * 2^e.
+ *   3. Shared exponent e = floor(log2(max|v|)) - emax clamped to the scale's range; elements are
+ *      rounded to the nearest magnitude, ties to the even code, saturating at the largest
+ *      magnitude; the sign bit is the input's sign bit.
+ *   4. Non-finite input, 8-bit scales: a block containing an Inf or NaN stores all-zero codes
+ *      and scale byte 255, and scale byte 255 decodes the whole block to NaN.  The NaN therefore
+ *      reaches the reduced output on every worker.
+ *   5. Non-finite input, scales narrower than 8 bits: there is NO marker.  A block containing an
+ *      Inf or NaN stores all-zero codes and the largest scale code, and decodes to zeros: the
+ *      non-finite value is LOST, silently, and the reduced output is finite.  With
+ *      mxc_dequant_reduce_own the worker that owns the block adds its raw Inf/NaN and gets a
+ *      non-finite sum while every other worker gets a finite one, so the replicas of the
+ *      reduced tensor differ in that block.  Callers that may see non-finite activations and
+ *      need them to propagate must use an 8-bit scale.
+ *   6. Packed codes: element j of a row occupies bits [j*b, (j+1)*b) of the row's little-endian
+ *      bit stream, rows back to back (hidden*b/8 bytes each).  Scales, s = 8: uint8 [tokens x
+ *      hidden/block], row-major.  Scales, s < 8: a bit stream over all blocks of the tensor in
+ *      the same order, block k at bits [k*s, (k+1)*s), LSB first, ceil(blocks*s/8) bytes, unused
+ *      bits of the last byte zero.
+ *   7. Every data pointer is a DEVICE pointer owned by the caller, valid until the stream has
+ *      finished the call.  Arrays of pointers (`const void* const*`) are HOST arrays of device
+ *      pointers; they are read during the call and need not outlive it.  The library cannot see
+ *      buffer sizes: a buffer shorter than the shape implies is read or written past its end.
+ *   8. `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Each call
+ *      validates its arguments on the host, enqueues one kernel on that stream and returns
+ *      without synchronising.  The library allocates nothing and keeps no state (other than the
+ *      pair of events mxc_time_next_launch arms for one launch of the calling thread).
+ *   9. Return value: MXC_OK or a negative mxc_status.  On error nothing has been enqueued.  A
+ *      valid call on an empty tensor (tokens == 0) enqueues nothing and returns MXC_OK.
+ *      MXC_ERR_HIP reports the launch call's own return value; the thread's HIP error state is
+ *      neither read nor cleared.
+ *  10. Alignment: bf16/f32 tensors and packed code arrays must be 16-byte aligned, scale arrays
+ *      4-byte aligned (MXC_ERR_ALIGN otherwise).  A requantize chunk's rows start at multiples of
+ *      tokens/tp rows, which keeps this alignment for every supported shape.
  */
 #ifndef MXC_H
 #define MXC_H
@@ -118,7 +131,8 @@ int mxc_dequant_reduce(const mxc_format *fmt, int tp, const void *const *codes,
  * the term of rank own_rank (0..tp-1) is read from own_x_bf16 (device, bf16 [tokens x hidden],
  * exact in binary32) instead of being decoded; codes[own_rank] / scales[own_rank] are not read
  * and may be NULL.  The order of the adds is still rank order, so the result differs between
- * ranks only through which term is exact. */
+ * ranks only through which term is exact (and, with scales narrower than 8 bits, in blocks that
+ * held an Inf or NaN: rule 5). */
 int mxc_dequant_reduce_own(const mxc_format *fmt, int tp, int own_rank, const void *own_x_bf16,
                            const void *const *codes, const void *const *scales, int64_t tokens,
                            int64_t hidden, void *out, int out_dtype, void *hip_stream);
@@ -153,7 +167,8 @@ int mxc_copy_probe(void *dst, const void *src, size_t bytes, void *hip_stream);
  * stop_event when it ends, from the dispatch's own timestamps, so hipEventElapsedTime between
  * them is the kernel's duration without the launch gap, and no extra packet enters the stream.
  * The pair is used once and then forgotten; a call that fails validation launches nothing and
- * leaves it armed; (NULL, NULL) disarms.  Do not arm events for launches under stream capture.
+ * leaves it armed; a valid call on an empty tensor launches nothing and disarms it; (NULL, NULL)
+ * disarms.  Do not arm events for launches under stream capture.
  * Always returns MXC_OK. */
 int mxc_time_next_launch(void *start_event, void *stop_event);
 

@@ -217,3 +217,26 @@ def round_to_bf16(x: np.ndarray) -> np.ndarray:
     out = np.empty(x.shape, dtype=np.uint16)
     _check(lib().mxo_round_to_bf16(_ptr(x), ctypes.c_int64(x.size), _ptr(out)), "round_to_bf16")
     return out
+
+
+def sum_bf16(parts) -> np.ndarray:
+    """The uncompressed reduction: binary32 left fold, in list order, of bf16 partials given as
+    uint16 bit patterns (Profiling)."""
+    ps = [np.ascontiguousarray(p, dtype=np.uint16) for p in parts]
+    out = np.empty(ps[0].shape, dtype=np.float32)
+    pp = (ctypes.c_void_p * len(ps))(*[p.ctypes.data for p in ps])
+    _check(lib().mxo_sum_bf16(ctypes.c_int(len(ps)), pp, ctypes.c_int64(ps[0].size), _ptr(out)),
+           "sum_bf16")
+    return out
+
+
+def sqnr_db(ref: np.ndarray, test: np.ndarray) -> float:
+    """Quality proxy: SQNR in dB of ``test`` against ``ref`` (stands in for Model Evaluation's
+    perplexity increase)."""
+    ref = np.ascontiguousarray(ref, dtype=np.float32)
+    test = np.ascontiguousarray(test, dtype=np.float32)
+    assert ref.shape == test.shape
+    out = ctypes.c_double()
+    _check(lib().mxo_sqnr_db(_ptr(ref), _ptr(test), ctypes.c_int64(ref.size), ctypes.byref(out)),
+           "sqnr_db")
+    return out.value

@@ -446,3 +446,39 @@ int mxo_round_to_bf16(const float *x, int64_t n, uint16_t *out)
     for (int64_t i = 0; i < n; ++i) out[i] = bf16_from_float(x[i]);
     return MXO_OK;
 }
+
+/* The uncompressed reduction the method is compared with (Profiling: without compression the
+ * partials are reduced as they are): out = (((x_0 + x_1) + x_2) + ...), binary32 adds in rank
+ * order of the bfloat16 partials. */
+int mxo_sum_bf16(int tp, const uint16_t *const *x, int64_t n, float *out)
+{
+    if (tp < 1 || tp > 32) return MXO_ERR_TP;
+    if (n < 0) return MXO_ERR_SHAPE;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        volatile float acc = (float)bf16_value(x[0][i]);
+        for (int r = 1; r < tp; ++r) {
+            float a = acc;
+            acc = a + (float)bf16_value(x[r][i]);
+        }
+        out[i] = acc;
+    }
+    return MXO_OK;
+}
+
+/* Quality proxy for a compressed reduction: signal-to-quantization-noise ratio in dB of `test`
+ * against the uncompressed result `ref`, 10 log10( sum ref^2 / sum (test - ref)^2 ), both sums
+ * accumulated in doubles in index order.  It stands in for the perplexity increase the Model
+ * Evaluation section reports, which needs models and data.  Equal tensors give +infinity. */
+int mxo_sqnr_db(const float *ref, const float *test, int64_t n, double *out)
+{
+    if (n < 0) return MXO_ERR_SHAPE;
+    double signal = 0.0, noise = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        double r = (double)ref[i], d = (double)test[i] - r;
+        signal += r * r;
+        noise += d * d;
+    }
+    *out = noise > 0.0 ? 10.0 * log10(signal / noise) : INFINITY;
+    return MXO_OK;
+}

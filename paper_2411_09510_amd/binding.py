@@ -115,9 +115,15 @@ def _stream(stream) -> ctypes.c_void_p:
     return ctypes.c_void_p(s.cuda_stream)
 
 
-def _dev(t: torch.Tensor, dtype, what: str) -> torch.Tensor:
+def _p(t: torch.Tensor) -> int:
+    """Device address of a tensor; every pointer handed to the library goes through here, after
+    the shape and size checks."""
     if not t.is_cuda:
-        raise ValueError(f"{what} must be a device tensor")
+        raise ValueError("the library takes device tensors only, got one on " + str(t.device))
+    return t.data_ptr()
+
+
+def _dev(t: torch.Tensor, dtype, what: str) -> torch.Tensor:
     if t.dtype != dtype:
         raise ValueError(f"{what} must be {dtype}, got {t.dtype}")
     if not t.is_contiguous():
@@ -125,8 +131,28 @@ def _dev(t: torch.Tensor, dtype, what: str) -> torch.Tensor:
     return t
 
 
+def _sized(t: torch.Tensor, dtype, nbytes: int, what: str) -> torch.Tensor:
+    """A device tensor of ``dtype``, contiguous, holding exactly ``nbytes`` bytes: the library
+    takes raw pointers, so this is the only place a short or misshapen buffer can be caught
+    before a kernel reads or writes past it."""
+    if t.dtype != dtype:
+        raise ValueError(f"{what} must be {dtype}, got {t.dtype}")
+    have = t.numel() * t.element_size()
+    if have != nbytes:
+        raise ValueError(f"{what} holds {have} bytes, the call needs {nbytes}")
+    return _dev(t, dtype, what)
+
+
+def _packed_ok(fmt: "Format", tokens: int, hidden: int, codes, scales, what: str = "") -> None:
+    """Every (codes, scales) pair has the packed sizes of a [tokens, hidden] tensor."""
+    cb, sb = packed_sizes(fmt, tokens, hidden)
+    for c, s_ in zip(codes, scales):
+        _sized(c, torch.uint8, cb, what + "codes")
+        _sized(s_, torch.uint8, sb, what + "scales")
+
+
 def _ptrs(ts: Sequence[torch.Tensor]):
-    return (ctypes.c_void_p * len(ts))(*[t.data_ptr() for t in ts])
+    return (ctypes.c_void_p * len(ts))(*[_p(t) for t in ts])
 
 
 def packed_sizes(fmt: Format, tokens: int, hidden: int) -> Tuple[int, int]:
@@ -165,22 +191,41 @@ def quantize(fmt: Format, x: torch.Tensor, codes: Optional[torch.Tensor] = None,
     tokens, hidden = x.shape
     if codes is None or scales is None:
         codes, scales = _alloc_packed(fmt, tokens, hidden, x.device)
+    _packed_ok(fmt, tokens, hidden, [codes], [scales])
     f = fmt.c()
-    _check(lib().mxc_quantize(ctypes.byref(f), x.data_ptr(), tokens, hidden, codes.data_ptr(),
-                              scales.data_ptr(), _stream(stream)), "mxc_quantize")
+    _check(lib().mxc_quantize(ctypes.byref(f), _p(x), tokens, hidden, _p(codes),
+                              _p(scales), _stream(stream)), "mxc_quantize")
     return codes, scales
+
+
+def _same_shape(xs: Sequence[torch.Tensor]) -> Tuple[int, int]:
+    """bf16 device tensors that all have the shape of the first, which is returned."""
+    if len(xs) == 0:
+        raise ValueError("no tensors given")
+    for x in xs:
+        if x.dim() != 2 or x.shape != xs[0].shape:
+            raise ValueError(f"all partials must have one 2-D shape, got {tuple(x.shape)} and "
+                             f"{tuple(xs[0].shape)}")
+    for x in xs:
+        _dev(x, torch.bfloat16, "x")
+    return int(xs[0].shape[0]), int(xs[0].shape[1])
+
+
+def _lists_match(*lists) -> None:
+    if len({len(l) for l in lists}) != 1:
+        raise ValueError("the tensor lists of one call must have the same length")
 
 
 def quantize_batched(fmt: Format, xs: Sequence[torch.Tensor],
                      codes: Optional[List[torch.Tensor]] = None,
                      scales: Optional[List[torch.Tensor]] = None, stream=None):
     """The same for several partials of one shape in a single launch."""
-    for x in xs:
-        _dev(x, torch.bfloat16, "x")
-    tokens, hidden = xs[0].shape
+    tokens, hidden = _same_shape(xs)
     if codes is None or scales is None:
         pairs = [_alloc_packed(fmt, tokens, hidden, xs[0].device) for _ in xs]
         codes, scales = [p[0] for p in pairs], [p[1] for p in pairs]
+    _lists_match(xs, codes, scales)
+    _packed_ok(fmt, tokens, hidden, codes, scales)
     f = fmt.c()
     _check(lib().mxc_quantize_batched(ctypes.byref(f), len(xs), _ptrs(xs), tokens, hidden,
                                       _ptrs(codes), _ptrs(scales), _stream(stream)),
@@ -188,19 +233,26 @@ def quantize_batched(fmt: Format, xs: Sequence[torch.Tensor],
     return codes, scales
 
 
+def _out_dtype(out: torch.Tensor, tokens: int, hidden: int) -> int:
+    """Checks a reduction's output tensor and returns its mxc_dtype."""
+    if out.dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError("out must be float32 or bfloat16")
+    _sized(out, out.dtype, tokens * hidden * out.element_size(), "out")
+    return MXC_F32 if out.dtype == torch.float32 else MXC_BF16
+
+
 def dequant_reduce(fmt: Format, codes: Sequence[torch.Tensor], scales: Sequence[torch.Tensor],
                    tokens: int, hidden: int, out: Optional[torch.Tensor] = None,
                    out_dtype=torch.float32, stream=None) -> torch.Tensor:
     """Decode the partials and add them in list order with float32 adds."""
-    for c, s in zip(codes, scales):
-        _dev(c, torch.uint8, "codes")
-        _dev(s, torch.uint8, "scales")
+    _lists_match(codes, scales)
+    _packed_ok(fmt, tokens, hidden, codes, scales)
     if out is None:
         out = torch.empty((tokens, hidden), dtype=out_dtype, device=codes[0].device)
-    dt = {torch.float32: MXC_F32, torch.bfloat16: MXC_BF16}[out.dtype]
+    dt = _out_dtype(out, tokens, hidden)
     f = fmt.c()
     _check(lib().mxc_dequant_reduce(ctypes.byref(f), len(codes), _ptrs(codes), _ptrs(scales),
-                                    tokens, hidden, out.data_ptr(), dt, _stream(stream)),
+                                    tokens, hidden, _p(out), dt, _stream(stream)),
            "mxc_dequant_reduce")
     return out
 
@@ -214,11 +266,14 @@ def requantize_chunk(fmt: Format, reduced: torch.Tensor, tp: int, chunk: int,
     _dev(reduced, reduced.dtype, "reduced")
     tokens, hidden = reduced.shape
     dt = MXC_F32 if reduced.dtype == torch.float32 else MXC_BF16
+    if tp < 1 or tokens % tp:
+        raise ValueError("tokens must be a multiple of tp")
     if codes is None or scales is None:
-        codes, scales = _alloc_packed(fmt, tokens // max(tp, 1), hidden, reduced.device)
+        codes, scales = _alloc_packed(fmt, tokens // tp, hidden, reduced.device)
+    _packed_ok(fmt, tokens // tp, hidden, [codes], [scales])
     f = fmt.c()
-    _check(lib().mxc_requantize_chunk(ctypes.byref(f), reduced.data_ptr(), dt, tokens, hidden, tp,
-                                      chunk, codes.data_ptr(), scales.data_ptr(),
+    _check(lib().mxc_requantize_chunk(ctypes.byref(f), _p(reduced), dt, tokens, hidden, tp,
+                                      chunk, _p(codes), _p(scales),
                                       _stream(stream)), "mxc_requantize_chunk")
     return codes, scales
 
@@ -231,18 +286,17 @@ def dequant_reduce_own(fmt: Format, own_rank: int, own_x: torch.Tensor,
     ``codes[own_rank]`` / ``scales[own_rank]`` may be None."""
     _dev(own_x, torch.bfloat16, "own_x")
     tokens, hidden = own_x.shape
-    for r, (c, s_) in enumerate(zip(codes, scales)):
-        if r != own_rank:
-            _dev(c, torch.uint8, "codes")
-            _dev(s_, torch.uint8, "scales")
+    _lists_match(codes, scales)
+    others = [r for r in range(len(codes)) if r != own_rank]
+    _packed_ok(fmt, tokens, hidden, [codes[r] for r in others], [scales[r] for r in others])
     if out is None:
         out = torch.empty((tokens, hidden), dtype=out_dtype, device=own_x.device)
-    dt = {torch.float32: MXC_F32, torch.bfloat16: MXC_BF16}[out.dtype]
-    cp = (ctypes.c_void_p * len(codes))(*[None if c is None else c.data_ptr() for c in codes])
-    sp = (ctypes.c_void_p * len(codes))(*[None if s_ is None else s_.data_ptr() for s_ in scales])
+    dt = _out_dtype(out, tokens, hidden)
+    cp = (ctypes.c_void_p * len(codes))(*[None if c is None else _p(c) for c in codes])
+    sp = (ctypes.c_void_p * len(codes))(*[None if s_ is None else _p(s_) for s_ in scales])
     f = fmt.c()
-    _check(lib().mxc_dequant_reduce_own(ctypes.byref(f), len(codes), own_rank, own_x.data_ptr(),
-                                        cp, sp, tokens, hidden, out.data_ptr(), dt,
+    _check(lib().mxc_dequant_reduce_own(ctypes.byref(f), len(codes), own_rank, _p(own_x),
+                                        cp, sp, tokens, hidden, _p(out), dt,
                                         _stream(stream)), "mxc_dequant_reduce_own")
     return out
 
@@ -253,15 +307,15 @@ def dequant_reduce_requantize(fmt: Format, codes: Sequence[torch.Tensor],
                               scales_out: Optional[torch.Tensor] = None, stream=None):
     """Fused dequant-reduce + requantize of a row chunk: the tp compressed copies of a
     [tokens, hidden] chunk in, the packed arrays of the re-quantized sum out."""
-    for c, s_ in zip(codes, scales):
-        _dev(c, torch.uint8, "codes")
-        _dev(s_, torch.uint8, "scales")
+    _lists_match(codes, scales)
+    _packed_ok(fmt, tokens, hidden, codes, scales)
     if codes_out is None or scales_out is None:
         codes_out, scales_out = _alloc_packed(fmt, tokens, hidden, codes[0].device)
+    _packed_ok(fmt, tokens, hidden, [codes_out], [scales_out], "output ")
     f = fmt.c()
     _check(lib().mxc_dequant_reduce_requantize(ctypes.byref(f), len(codes), _ptrs(codes),
                                                _ptrs(scales), tokens, hidden,
-                                               codes_out.data_ptr(), scales_out.data_ptr(),
+                                               _p(codes_out), _p(scales_out),
                                                _stream(stream)), "mxc_dequant_reduce_requantize")
     return codes_out, scales_out
 
@@ -285,12 +339,9 @@ class Launch:
 
 def prepare_quantize_batched(fmt: Format, xs: Sequence[torch.Tensor],
                              codes: Sequence[torch.Tensor], scales: Sequence[torch.Tensor]) -> Launch:
-    for x in xs:
-        _dev(x, torch.bfloat16, "x")
-    for c, s_ in zip(codes, scales):
-        _dev(c, torch.uint8, "codes")
-        _dev(s_, torch.uint8, "scales")
-    tokens, hidden = xs[0].shape
+    tokens, hidden = _same_shape(xs)
+    _lists_match(xs, codes, scales)
+    _packed_ok(fmt, tokens, hidden, codes, scales)
     f = fmt.c()
     args = (ctypes.byref(f), len(xs), _ptrs(xs), tokens, hidden, _ptrs(codes), _ptrs(scales))
     return Launch(lib().mxc_quantize_batched, args, (f, list(xs), list(codes), list(scales)),
@@ -300,14 +351,12 @@ def prepare_quantize_batched(fmt: Format, xs: Sequence[torch.Tensor],
 def prepare_dequant_reduce(fmt: Format, codes: Sequence[torch.Tensor],
                            scales: Sequence[torch.Tensor], tokens: int, hidden: int,
                            out: torch.Tensor) -> Launch:
-    for c, s_ in zip(codes, scales):
-        _dev(c, torch.uint8, "codes")
-        _dev(s_, torch.uint8, "scales")
-    _dev(out, out.dtype, "out")
-    dt = {torch.float32: MXC_F32, torch.bfloat16: MXC_BF16}[out.dtype]
+    _lists_match(codes, scales)
+    _packed_ok(fmt, tokens, hidden, codes, scales)
+    dt = _out_dtype(out, tokens, hidden)
     f = fmt.c()
     args = (ctypes.byref(f), len(codes), _ptrs(codes), _ptrs(scales), tokens, hidden,
-            out.data_ptr(), dt)
+            _p(out), dt)
     return Launch(lib().mxc_dequant_reduce, args, (f, list(codes), list(scales), out),
                   "mxc_dequant_reduce")
 
@@ -315,12 +364,12 @@ def prepare_dequant_reduce(fmt: Format, codes: Sequence[torch.Tensor],
 def prepare_dequant_reduce_requantize(fmt: Format, codes: Sequence[torch.Tensor],
                                       scales: Sequence[torch.Tensor], tokens: int, hidden: int,
                                       codes_out: torch.Tensor, scales_out: torch.Tensor) -> Launch:
-    for c, s_ in zip(codes, scales):
-        _dev(c, torch.uint8, "codes")
-        _dev(s_, torch.uint8, "scales")
+    _lists_match(codes, scales)
+    _packed_ok(fmt, tokens, hidden, codes, scales)
+    _packed_ok(fmt, tokens, hidden, [codes_out], [scales_out], "output ")
     f = fmt.c()
     args = (ctypes.byref(f), len(codes), _ptrs(codes), _ptrs(scales), tokens, hidden,
-            codes_out.data_ptr(), scales_out.data_ptr())
+            _p(codes_out), _p(scales_out))
     return Launch(lib().mxc_dequant_reduce_requantize, args,
                   (f, list(codes), list(scales), codes_out, scales_out),
                   "mxc_dequant_reduce_requantize")
@@ -328,19 +377,26 @@ def prepare_dequant_reduce_requantize(fmt: Format, codes: Sequence[torch.Tensor]
 
 def prepare_requantize_chunk(fmt: Format, reduced: torch.Tensor, tp: int, chunk: int,
                              codes: torch.Tensor, scales: torch.Tensor) -> Launch:
+    if reduced.dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError("reduced must be float32 or bfloat16")
     _dev(reduced, reduced.dtype, "reduced")
     tokens, hidden = reduced.shape
     dt = MXC_F32 if reduced.dtype == torch.float32 else MXC_BF16
+    if tp < 1 or tokens % tp:
+        raise ValueError("tokens must be a multiple of tp")
+    _packed_ok(fmt, tokens // tp, hidden, [codes], [scales])
     f = fmt.c()
-    args = (ctypes.byref(f), reduced.data_ptr(), dt, tokens, hidden, tp, chunk,
-            codes.data_ptr(), scales.data_ptr())
+    args = (ctypes.byref(f), _p(reduced), dt, tokens, hidden, tp, chunk,
+            _p(codes), _p(scales))
     return Launch(lib().mxc_requantize_chunk, args, (f, reduced, codes, scales),
                   "mxc_requantize_chunk")
 
 
 def copy_probe(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    _dev(src, src.dtype, "src")
     nbytes = src.numel() * src.element_size()
-    _check(lib().mxc_copy_probe(dst.data_ptr(), src.data_ptr(), nbytes, _stream(stream)),
+    _sized(dst, dst.dtype, nbytes, "dst")
+    _check(lib().mxc_copy_probe(_p(dst), _p(src), nbytes, _stream(stream)),
            "mxc_copy_probe")
 
 

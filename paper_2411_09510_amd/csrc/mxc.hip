@@ -47,6 +47,14 @@ int shape_units(const mxc_format *f, int64_t tokens, int64_t hidden, size_t *uni
     return MXC_OK;
 }
 
+// A valid call on an empty tensor: nothing to launch, so events armed for "the next launch" would
+// otherwise stamp some later, unrelated kernel.
+int empty_ok()
+{
+    disarm();
+    return MXC_OK;
+}
+
 bool aligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
 int quantize_common(const mxc_format *fmt, int n, const void *const *x, bool src32,
@@ -64,7 +72,7 @@ int quantize_common(const mxc_format *fmt, int n, const void *const *x, bool src
         if (!aligned(x[i], 16) || !aligned(codes[i], 16) || !aligned(scales[i], 4))
             return MXC_ERR_ALIGN;
     }
-    if (a.units == 0) return MXC_OK;
+    if (a.units == 0) return empty_ok();
     for (int i = 0; i < 32; ++i) {
         const int k = i < n ? i : 0;
         a.x[i] = x[k];
@@ -175,7 +183,7 @@ int mxc_dequant_reduce(const mxc_format *fmt, int tp, const void *const *codes,
     int rc = reduce_args(fmt, tp, codes, scales, tokens, hidden, &a);
     if (rc != MXC_OK) return rc;
     if (!aligned(out, 16)) return MXC_ERR_ALIGN;
-    if (a.units == 0) return MXC_OK;
+    if (a.units == 0) return empty_ok();
     a.out = out;
     return out_dtype == MXC_BF16 ? reduce_to_bf16(fmt, a, (hipStream_t)hip_stream)
                                  : reduce_to_f32(fmt, a, (hipStream_t)hip_stream);
@@ -193,7 +201,7 @@ int mxc_dequant_reduce_own(const mxc_format *fmt, int tp, int own_rank, const vo
     int rc = reduce_args(fmt, tp, codes, scales, tokens, hidden, &a, own_rank, own_x_bf16);
     if (rc != MXC_OK) return rc;
     if (!aligned(out, 16) || !aligned(own_x_bf16, 16)) return MXC_ERR_ALIGN;
-    if (a.units == 0) return MXC_OK;
+    if (a.units == 0) return empty_ok();
     a.out = out;
     return out_dtype == MXC_BF16 ? reduce_own_to_bf16(fmt, a, (hipStream_t)hip_stream)
                                  : reduce_own_to_f32(fmt, a, (hipStream_t)hip_stream);
@@ -209,7 +217,7 @@ int mxc_dequant_reduce_requantize(const mxc_format *fmt, int tp, const void *con
     if (rc != MXC_OK) return rc;
     if (a.units % 4) return MXC_ERR_SHAPE;
     if (!aligned(codes_out, 16) || !aligned(scales_out, 4)) return MXC_ERR_ALIGN;
-    if (a.units == 0) return MXC_OK;
+    if (a.units == 0) return empty_ok();
     a.codes_out = codes_out;
     a.scales_out = scales_out;
     return reduce_requantize(fmt, a, (hipStream_t)hip_stream);
@@ -242,7 +250,7 @@ int mxc_copy_probe(void *dst, const void *src, size_t bytes, void *hip_stream)
     if (!dst || !src) return MXC_ERR_NULL;
     if (bytes % 16) return MXC_ERR_SHAPE;
     if (!aligned(dst, 16) || !aligned(src, 16)) return MXC_ERR_ALIGN;
-    if (bytes == 0) return MXC_OK;
+    if (bytes == 0) return empty_ok();
     const size_t n16 = bytes / 16;
     return launch(copy_kernel<kCopyU, false>, dim3(grid_for(n16, kCopyU)), (hipStream_t)hip_stream,
                   (u32x4 *)dst, (const u32x4 *)src, n16);

@@ -51,19 +51,28 @@ inline unsigned grid_for(size_t units, int per_lane)
 // Events armed by mxc_time_next_launch for the calling thread; the next launch consumes them.
 extern thread_local hipEvent_t t_start, t_stop;
 
+// Drops the events armed by mxc_time_next_launch (used where a call ends without a launch).
+inline void disarm()
+{
+    t_start = t_stop = nullptr;
+}
+
 // Every kernel of the library is enqueued here.  With armed events the launch goes through the
 // extended launch call, which stamps them from the dispatch's own begin and end timestamps and
-// adds no packet to the stream.
+// adds no packet to the stream.  The status is the launch call's own return value: the thread's
+// sticky error state, which other users of the runtime share, is neither read nor cleared.
 template <class... Args>
 int launch(void (*kernel)(Args...), dim3 grid, hipStream_t st, Args... args)
 {
+    void *argv[] = {(void *)&args...};
+    hipError_t err;
     if (t_start || t_stop) {
-        hipExtLaunchKernelGGL(kernel, grid, dim3(kThreads), 0, st, t_start, t_stop, 0, args...);
-        t_start = t_stop = nullptr;
+        err = hipExtLaunchKernel((const void *)kernel, grid, dim3(kThreads), argv, 0, st, t_start, t_stop, 0);
+        disarm();
     } else {
-        hipLaunchKernelGGL(kernel, grid, dim3(kThreads), 0, st, args...);
+        err = hipLaunchKernel((const void *)kernel, grid, dim3(kThreads), argv, 0, st);
     }
-    return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_HIP;
+    return err == hipSuccess ? MXC_OK : MXC_ERR_HIP;
 }
 
 // Calls fn(Elem<x, y>{}, std::integral_constant<int, block>{}) for the format's element type and

@@ -116,6 +116,57 @@ def test_binding_refuses_host_tensors():
         mxc.quantize(mxc.Format(2, 1), torch.zeros(4, 64, dtype=torch.bfloat16))
 
 
+def test_binding_refuses_buffers_of_the_wrong_size():
+    """The binding is the only layer that knows buffer sizes: a short, long or misshapen buffer
+    raises before anything is launched (checked here with host tensors: the size check comes
+    before the device check, so no GPU is needed)."""
+    import torch
+    import paper_2411_09510_amd as mxc
+    f = mxc.Format(2, 1, 32, 8)
+    T, H = 4, 64
+    cb, sb = mxc.packed_sizes(f, T, H)
+    u8 = lambda n: torch.zeros(n, dtype=torch.uint8)
+    x = torch.zeros(T, H, dtype=torch.bfloat16)
+    size = "holds .* bytes"
+    with pytest.raises(ValueError, match=size):
+        mxc.quantize(f, x, u8(cb - 1), u8(sb))
+    with pytest.raises(ValueError, match=size):
+        mxc.quantize(f, x, u8(cb), u8(sb + 1))
+    with pytest.raises(ValueError, match="one 2-D shape"):
+        mxc.quantize_batched(f, [x, torch.zeros(T, 2 * H, dtype=torch.bfloat16)])
+    with pytest.raises(ValueError, match="same length"):
+        mxc.quantize_batched(f, [x, x], [u8(cb)], [u8(sb), u8(sb)])
+    with pytest.raises(ValueError, match=size):
+        mxc.dequant_reduce(f, [u8(cb), u8(cb // 2)], [u8(sb), u8(sb)], T, H)
+    with pytest.raises(ValueError, match=size):
+        mxc.dequant_reduce(f, [u8(cb)], [u8(sb)], 2 * T, H)                  # caller's shape is wrong
+    with pytest.raises(ValueError, match=size):
+        mxc.dequant_reduce(f, [u8(cb)], [u8(sb)], T, H, out=torch.zeros(T, H // 2))
+    with pytest.raises(ValueError, match="float32 or bfloat16"):
+        mxc.dequant_reduce(f, [u8(cb)], [u8(sb)], T, H, out=torch.zeros(T, H, dtype=torch.float16))
+    with pytest.raises(ValueError, match=size):
+        mxc.dequant_reduce_own(f, 0, x, [None, u8(cb + 16)], [None, u8(sb)])
+    with pytest.raises(ValueError, match=size):
+        mxc.dequant_reduce_requantize(f, [u8(cb)], [u8(sb)], T, H, u8(cb), u8(sb - 1))
+    with pytest.raises(ValueError, match=size):
+        mxc.requantize_chunk(f, torch.zeros(T, H), 2, 0, u8(cb), u8(sb))     # a chunk is half of that
+    with pytest.raises(ValueError, match="multiple of tp"):
+        mxc.requantize_chunk(f, torch.zeros(T, H), 3, 0)
+    with pytest.raises(ValueError, match=size):
+        mxc.prepare_dequant_reduce(f, [u8(cb)], [u8(sb)], T, H, torch.zeros(T + 1, H))
+    with pytest.raises(ValueError, match=size):
+        mxc.prepare_quantize_batched(f, [x], [u8(cb)], [u8(2 * sb)])
+    with pytest.raises(ValueError, match=size):
+        mxc.prepare_dequant_reduce_requantize(f, [u8(cb)], [u8(sb)], T, H, u8(1), u8(sb))
+    with pytest.raises(ValueError, match=size):
+        mxc.prepare_requantize_chunk(f, torch.zeros(T, H), 1, 0, u8(cb), u8(1))
+    with pytest.raises(ValueError, match=size):
+        mxc.copy_probe(u8(16), u8(32))
+    # right sizes get as far as the device check
+    with pytest.raises(ValueError, match="device tensors only"):
+        mxc.dequant_reduce(f, [u8(cb)], [u8(sb)], T, H, out=torch.zeros(T, H))
+
+
 def test_integer_types_are_one_bit_exponent_floats(oracle_mod):
     """INT3/4/5 (Method, parameter list) = E1M1/E1M2/E1M3: a uniform symmetric grid."""
     import paper_2411_09510_amd as mxc

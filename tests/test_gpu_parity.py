@@ -630,6 +630,86 @@ def test_calls_can_be_captured_in_a_hip_graph(mxc, oracle_mod):
         assert torch.equal(eager, out)
 
 
+def test_narrow_scales_lose_non_finite_blocks_like_the_oracle(mxc, oracle_mod):
+    """Rule 5 of the library's contract: with scales narrower than 8 bits a block that held a
+    NaN decodes to zeros, so the all-decoded reduction is finite on every worker and the own-raw
+    reduction is NaN only on the worker that owns the NaN.  GPU = oracle in every case."""
+    T, H, B = 4, 2048, 32
+    w = workloads.Workload("nf", 2, T, H, seed=77)
+    parts = [workloads.partial_bf16(w, r) for r in range(2)]
+    parts[0][1, 40] = 0x7FC0
+    parts[0][2, 1000] = 0xFF80
+    xs = [dev_bf16(p) for p in parts]
+    for s in (5, 8):
+        fo, fg = oracle_mod.Format(2, 2, B, s), mxc.Format(2, 2, B, s)
+        codes, scales = mxc.quantize_batched(fg, xs)
+        ocs, oss = zip(*[oracle_mod.quantize_bf16(fo, p) for p in parts])
+        out = host(mxc.dequant_reduce(fg, codes, scales, T, H))
+        own = [host(mxc.dequant_reduce_own(fg, r, xs[r], codes, scales)) for r in range(2)]
+        torch.cuda.synchronize()
+        assert same_f32(out, oracle_mod.dequant_reduce(fo, list(ocs), list(oss)))
+        for r in range(2):
+            assert same_f32(own[r], oracle_mod.dequant_reduce_own(fo, r, parts[r], list(ocs), list(oss)))
+        if s == 8:
+            assert np.isnan(out[1, 32:64]).all() and np.isnan(own[1][1, 32:64]).all()
+        else:
+            assert np.isfinite(out).all() and np.isfinite(own[1]).all()
+            assert np.isnan(own[0][1, 40]) and np.isinf(own[0][2, 1000])
+
+
+def test_an_empty_call_disarms_the_timing_events(mxc, oracle_mod):
+    """Events armed for "the next launch" are dropped by a valid call on an empty tensor, so
+    they do not stamp a later, unrelated kernel."""
+    fg = mxc.Format(2, 1, 32, 8)
+    w = workloads.small_like(workloads.CONFIGS[3], 2048, 8192)
+    x = dev_bf16(workloads.partial_bf16(w, 0))
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    e1.record()
+    torch.cuda.synchronize()
+    empty = torch.empty((0, 8192), dtype=torch.bfloat16, device="cuda")
+    ce, se = torch.empty((0, 4096), dtype=torch.uint8, device="cuda"), torch.empty((0, 256), dtype=torch.uint8, device="cuda")
+    before = e0.elapsed_time(e1)
+    mxc.time_next_launch(e0, e1)
+    # torch gives an empty tensor a null data pointer; the ABI wants non-null ones, so hand it
+    # the addresses of a real buffer with zero rows
+    import ctypes
+    f = fg.c()
+    rc = mxc.lib().mxc_quantize(ctypes.byref(f), x.data_ptr(), 0, 8192, x.data_ptr(), x.data_ptr(), None)
+    assert rc == 0
+    del empty, ce, se
+    mxc.quantize(fg, x)                      # would have been stamped had the pair stayed armed
+    torch.cuda.synchronize()
+    assert e0.elapsed_time(e1) == before
+
+
+# ------------------------------------------------------------------------ quality proxy -----
+
+@pytest.mark.parametrize("x,y,B,s", [(2, 1, 32, 8), (2, 2, 32, 8), (3, 2, 32, 8), (2, 1, 32, 5), (2, 2, 8, 8)])
+def test_quality_proxy_of_the_gpu_pipeline_equals_the_oracle_pipeline(mxc, oracle_mod, x, y, B, s):
+    """SQNR of the reduced output against the uncompressed sum (the stand-in for the paper's
+    perplexity tables): the GPU pipeline's figure is the oracle pipeline's figure, and the
+    benchmark's own torch computation of it agrees."""
+    import bench
+    w = workloads.CONFIGS[1]
+    fo, fg = oracle_mod.Format(x, y, B, s), mxc.Format(x, y, B, s)
+    parts = [workloads.partial_bf16(w, r) for r in range(w.tp)]
+    xs = [dev_bf16(p) for p in parts]
+    codes, scales = mxc.quantize_batched(fg, xs)
+    out = mxc.dequant_reduce(fg, codes, scales, w.tokens, w.hidden)
+    torch.cuda.synchronize()
+    exact = oracle_mod.sum_bf16(parts)
+    ocs, oss = zip(*[oracle_mod.quantize_bf16(fo, p) for p in parts])
+    want = oracle_mod.sqnr_db(exact, oracle_mod.dequant_reduce(fo, list(ocs), list(oss)))
+    got = oracle_mod.sqnr_db(exact, host(out))
+    assert got == want and 5.0 < got < 40.0
+    exact_dev = xs[0].float()
+    for t in xs[1:]:
+        exact_dev += t.float()
+    assert np.array_equal(host(exact_dev).view(np.uint32), exact.view(np.uint32))
+    assert abs(bench.sqnr_db(torch, out, exact_dev) - want) < 1e-6
+
+
 # ------------------------------------------------------------------------ full size ---------
 
 def test_full_size_config3_whole_tensor(mxc, oracle_mod):

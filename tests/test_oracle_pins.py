@@ -463,12 +463,38 @@ def test_non_finite_blocks(oracle_mod):
         b = np.array([[0x3F80, bad, 0xC000, 0, 0, 0, 0, 0], [0x3F80] * 8], np.uint16)
         codes, scales = oracle_mod.quantize_bf16(fmt, b)
         assert scales[0, 0] == 255 and not codes[0].any()
-        assert scales[1, 0] == 125 and list(codes[1]) == [6] * 8 or scales[1, 0] == 125
+        # 1.0 with e = -2: p = 4.0, the E2M1 code of 4 is 6
+        assert scales[1, 0] == 125 and list(codes[1]) == [6] * 8
         out = oracle_mod.dequant_reduce(fmt, [codes], [scales])
         assert np.isnan(out[0]).all() and np.isfinite(out[1]).all()
     x = np.array([[1.0, np.inf, -2, 0, 0, 0, 0, 0]], np.float32)
     codes, scales = oracle_mod.quantize_f32(fmt, x)
     assert scales[0, 0] == 255 and not codes.any()
+
+
+def test_narrow_scales_lose_non_finite_blocks_and_own_raw_replicas_diverge(oracle_mod):
+    """Scales narrower than 8 bits have no marker: a block with a NaN stores zero codes and the
+    largest scale code and decodes to zeros.  The all-decoded reduction is then finite on every
+    worker; the own-raw reduction is NaN on the worker that owns the NaN and finite elsewhere."""
+    fmt = oracle_mod.Format(2, 1, 8, 5)
+    a = np.array([[0x3F80, 0x7FC0, 0xC000, 0, 0, 0, 0, 0] + [0x4000] * 8], np.uint16)   # NaN in block 0
+    b = np.array([[0x3F80] * 16], np.uint16)
+    ca, sa = oracle_mod.quantize_bf16(fmt, a)
+    cb, sb = oracle_mod.quantize_bf16(fmt, b)
+    assert sa[0, 0] == 31 and not ca[0, :8].any() and ca[0, 8:].all()
+    out = oracle_mod.dequant_reduce(fmt, [ca, cb], [sa, sb])
+    assert np.array_equal(out[0, :8], np.ones(8, np.float32)) and np.all(out[0, 8:] == 3.0)
+    own0 = oracle_mod.dequant_reduce_own(fmt, 0, a, [ca, cb], [sa, sb])
+    own1 = oracle_mod.dequant_reduce_own(fmt, 1, b, [ca, cb], [sa, sb])
+    assert np.isnan(own0[0, 1]) and np.isfinite(np.delete(own0[0], 1)).all()
+    assert np.isfinite(own1).all() and np.array_equal(own1, out)
+    # with an 8-bit scale the marker keeps every replica NaN in that block
+    fmt8 = oracle_mod.Format(2, 1, 8, 8)
+    ca, sa = oracle_mod.quantize_bf16(fmt8, a)
+    cb, sb = oracle_mod.quantize_bf16(fmt8, b)
+    for res in (oracle_mod.dequant_reduce(fmt8, [ca, cb], [sa, sb]),
+                oracle_mod.dequant_reduce_own(fmt8, 1, b, [ca, cb], [sa, sb])):
+        assert np.isnan(res[0, :8]).all() and np.all(res[0, 8:] == 3.0)
 
 
 def test_narrow_scale_formats_clamp_both_ends(oracle_mod):
@@ -642,6 +668,80 @@ def test_element_rounding_against_library_float8_casts(oracle_mod, x, y, f8):
     assert inside.mean() > 0.9
     assert np.array_equal(mag[inside], lib_mag[inside])
     assert np.all(mag[~inside] == magmask)                 # beyond the element format: saturated
+
+
+# ----------------------------------------------------------------- quality proxy ------------
+
+def test_uncompressed_sum_is_a_float32_left_fold(oracle_mod):
+    rng = np.random.default_rng(11)
+    parts = [workloads.f32_to_bf16_bits((rng.standard_normal((7, 96)) * 10.0 ** rng.integers(-3, 4))
+                                        .astype(np.float32)) for _ in range(5)]
+    got = oracle_mod.sum_bf16(parts)
+    acc = workloads.bf16_bits_to_f32(parts[0]).copy()
+    for p in parts[1:]:
+        acc = (acc + workloads.bf16_bits_to_f32(p)).astype(np.float32)      # numpy float32 adds
+    assert np.array_equal(got.view(np.uint32), acc.view(np.uint32))
+    exact = sum(workloads.bf16_bits_to_f32(p).astype(np.float64) for p in parts)
+    assert np.all(np.abs(got - exact) <= 5 * 2.0 ** -24 * sum(np.abs(workloads.bf16_bits_to_f32(p)) for p in parts))
+    # the order of the adds shows: 2^24 + 1 + 1 against 1 + 1 + 2^24
+    big, one = np.array([[0x4B80]], np.uint16), np.array([[0x3F80]], np.uint16)
+    assert oracle_mod.sum_bf16([big, one, one])[0, 0] == 2.0 ** 24
+    assert oracle_mod.sum_bf16([one, one, big])[0, 0] == 2.0 ** 24 + 2
+
+
+def test_sqnr_closed_forms(oracle_mod):
+    """SQNR pins: a relative error of 2^-k everywhere is 20 k log10(2) dB; an all-zero test
+    tensor is 0 dB; equal tensors are +inf; an error that is orthogonal to the signal and a
+    quarter of its power is 10 log10(4) dB."""
+    rng = np.random.default_rng(12)
+    ref = (rng.integers(1, 2 ** 12, size=(33, 64)) * rng.choice([-1.0, 1.0], size=(33, 64))).astype(np.float32)
+    for k in (1, 4, 9):
+        test = (ref.astype(np.float64) * (1.0 + 2.0 ** -k)).astype(np.float32)   # exact: 12 + k bits
+        assert abs(oracle_mod.sqnr_db(ref, test) - 20.0 * k * np.log10(2.0)) < 1e-9
+    assert abs(oracle_mod.sqnr_db(ref, np.zeros_like(ref))) < 1e-12
+    assert oracle_mod.sqnr_db(ref, ref) == float("inf")
+    a = np.zeros((2, 8), np.float32)
+    a[0] = 4.0
+    b = a.copy()
+    b[1] = 2.0                                   # noise power 8 * 4, signal power 8 * 16
+    assert abs(oracle_mod.sqnr_db(a, b) - 10.0 * np.log10(4.0)) < 1e-12
+    # not symmetric: the reference is the first argument
+    assert abs(oracle_mod.sqnr_db(b, a) - 10.0 * np.log10(5.0)) < 1e-12
+
+
+def oracle_pipeline_sqnr(oracle_mod, w, x, y, B, s, parts=None):
+    fo = oracle_mod.Format(x, y, B, s)
+    parts = parts if parts is not None else [workloads.partial_bf16(w, r) for r in range(w.tp)]
+    cs, ss = zip(*[oracle_mod.quantize_bf16(fo, p) for p in parts])
+    return oracle_mod.sqnr_db(oracle_mod.sum_bf16(parts), oracle_mod.dequant_reduce(fo, list(cs), list(ss)))
+
+
+def test_quality_trends_of_the_parameter_list(oracle_mod):
+    """The three trends the paper's perplexity tables show (Model Evaluation, Table 1; appendix
+    ablation table), on the quality proxy of the synthetic partials: a mantissa bit buys 5 to 7 dB
+    with a 2- or 3-bit exponent (3 to 4 dB on the uniform grids of a 1-bit exponent, where the
+    block's range rather than the step limits the error); smaller blocks are never worse; the
+    scale width does not matter down to E5M0."""
+    w = workloads.CONFIGS[1]
+    parts = [workloads.partial_bf16(w, r) for r in range(w.tp)]
+    q = lambda x, y, B=32, s=8: oracle_pipeline_sqnr(oracle_mod, w, x, y, B, s, parts)
+    # (1) one more mantissa bit at the same exponent width
+    for x, ys, lo, hi in ((1, (1, 2, 3, 4), 2.5, 6.0), (2, (1, 2, 3), 4.5, 7.5), (3, (1, 2), 4.5, 7.5)):
+        vals = [q(x, y) for y in ys]
+        for a, b in zip(vals, vals[1:]):
+            assert lo < b - a < hi, (x, ys, vals)
+    # (2) block 8 >= block 16 >= block 32 (the paper's Table 1: perplexity falls with block size)
+    for (x, y) in HOT_ELEMENTS + [(1, 2)]:
+        b8, b16, b32 = q(x, y, 8), q(x, y, 16), q(x, y, 32)
+        assert b8 >= b16 - 0.05 and b16 >= b32 - 0.05, (x, y, b8, b16, b32)
+    assert q(2, 1, 8) > q(2, 1, 32) + 0.5
+    # (3) scale formats E8M0 ... E5M0 give the same result (appendix ablation: identical rows)
+    for (x, y) in HOT_ELEMENTS:
+        ref = q(x, y, 32, 8)
+        for s in (7, 6, 5):
+            assert abs(q(x, y, 32, s) - ref) < 1e-9, (x, y, s)
+    # E2M1 / E2M2 / E3M2 at block 32 keep their order
+    assert q(2, 1) < q(2, 2) < q(3, 2)
 
 
 # ----------------------------------------------------------------------- generators ---------
