@@ -20,8 +20,6 @@ namespace host {
 constexpr int kQuantU = 2;          // units per lane, quantize from bf16
 constexpr int kQuantU32 = 1;        // units per lane, quantize from binary32 (LDS-transposed loads)
 constexpr bool kQuantNTL = true, kQuantNTS = true;
-constexpr int kReduceU = 4;         // units per lane, dequant-reduce
-constexpr int kReduceRC = 8;        // ranks loaded together, unit form
 // nontemporal stores: measured 5 % faster than plain ones whenever the outputs of successive
 // calls do not all fit the 256 MB last-level cache
 constexpr bool kReduceNTL = true, kReduceNTS = true;
@@ -132,19 +130,13 @@ int reduce_any(const mxc_format *f, const ReduceArgs &a, hipStream_t st)
     return for_format(f, [&](auto elem, auto block) {
         using E = decltype(elem);
         constexpr int B = decltype(block)::value;
-        if (a.units % 4 == 0) {
-            // whole 32-element chunks: one lane per chunk, output staged through LDS
-            const size_t chunks = a.units / 4;
-            const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads));
-            constexpr TileShape ts = tile_shape(E::bits, OUT_BF16, false, OWN);
-            return launch(dequant_reduce_tile_kernel<E, B, OUT_BF16, ts.rc, kReduceNTL, kReduceNTS, kHw,
-                                                     false, OWN, kThreads, ts.stage>,
-                          grid, st, a);
-        }
-        // sizes that are not a multiple of 32 elements (only possible with blocks of 8 or 16)
-        return launch(dequant_reduce_kernel<E, B, OUT_BF16, kReduceU, kReduceRC, kReduceNTL,
-                                            kReduceNTS, kHw, OWN>,
-                      dim3(grid_for(a.units, kReduceU)), st, a);
+        // one lane per 32-element chunk (the last chunk may be shorter), output staged through LDS
+        const size_t chunks = (a.units + 3) / 4;
+        const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads));
+        constexpr TileShape ts = tile_shape(E::bits, OUT_BF16, false, OWN);
+        return launch(dequant_reduce_tile_kernel<E, B, OUT_BF16, ts.rc, kReduceNTL, kReduceNTS, kHw,
+                                                 false, OWN, kThreads, ts.stage>,
+                      grid, st, a);
     });
 }
 

@@ -182,16 +182,6 @@ __device__ __forceinline__ void store_prefix(uint32_t *p, uint32_t v, int nbytes
     }
 }
 
-// Loads the first `nbytes` bytes of the dword at p; the rest reads as zero.
-template <bool NT>
-__device__ __forceinline__ uint32_t load_prefix(const uint32_t *p, int nbytes)
-{
-    if (nbytes >= 4) return ld<NT>(p);
-    uint32_t v = 0;
-    for (int k = 0; k < nbytes; ++k) v |= (uint32_t)((const uint8_t *)p)[k] << (8 * k);
-    return v;
-}
-
 // Store: lane holds its 8 codes in the low 8b bits of v (zero for a unit past the end).  After
 // the in-quad exchange each lane owns up to two whole dwords of the stream (k0, k1; -1 = none).
 template <int BITS, bool NT>
@@ -249,53 +239,6 @@ __device__ __forceinline__ void store_codes(uint32_t *codes, size_t unit, uint64
         const int vb = quad_valid_bytes(unit, units_total, BITS);
         if (k0 >= 0) store_prefix<NT>(q + k0, d0, vb - 4 * k0);
         if (k1 >= 0) store_prefix<NT>(q + k1, d1, vb - 4 * k1);
-    }
-}
-
-// Load: returns the lane's 8 codes in the low 8b bits (zero for a unit past the end, or when
-// `on` is false for the whole wave step, e.g. a rank beyond tp).  TAIL = false promises that no
-// lane of the wave step sits in the tensor's last, partial quad, and leaves that path out.
-template <int BITS, bool NT, bool TAIL = true>
-__device__ __forceinline__ uint64_t load_codes(const uint32_t *codes, size_t unit, size_t units_total, bool on)
-{
-    const int i = (int)(threadIdx.x & 3);
-    if (BITS == 4) return (on && unit < units_total) ? ld<NT>(codes + unit) : 0u;
-    // the dwords this lane fetches (k0, k1; -1 = none)
-    int k0 = -1, k1 = -1;
-    if (BITS == 5) {
-        k0 = i;
-        k1 = i == 0 ? 4 : -1;
-    } else if (BITS == 6) {
-        const int p0 = 3 * (i >> 1);
-        k0 = (i & 1) ? p0 + 1 : p0;
-        k1 = (i & 1) ? p0 + 2 : -1;
-    } else {
-        k0 = i < 3 ? i : -1;
-    }
-    const uint32_t *q = codes + (unit >> 2) * BITS;
-    uint32_t a = 0, b = 0;
-    if (on && (unit | 3) < units_total) {                         // the whole quad is inside
-        if (k0 >= 0) a = ld<NT>(q + k0);
-        if (k1 >= 0) b = ld<NT>(q + k1);
-    } else if (TAIL && on) {
-        const int vb = quad_valid_bytes(unit, units_total, BITS);
-        if (k0 >= 0) a = load_prefix<NT>(q + k0, vb - 4 * k0);
-        if (k1 >= 0) b = load_prefix<NT>(q + k1, vb - 4 * k1);
-    }
-    if (BITS == 5) {
-        uint32_t give = i ? a : b;
-        uint32_t next = dpp<quad_perm(1, 2, 3, 0)>(give);         // lane i gets dword i+1
-        uint64_t w = ((uint64_t)next << 32) | a;
-        return (w >> (8 * i)) & ((1ull << 40) - 1);
-    } else if (BITS == 6) {
-        uint32_t other = dpp<quad_perm(1, 0, 3, 2)>(a);           // even lane gets dword 1
-        uint64_t even = (uint64_t)a | ((uint64_t)(other & 0xFFFFu) << 32);
-        uint64_t odd = (uint64_t)(a >> 16) | ((uint64_t)b << 16);
-        return (i & 1) ? odd : even;
-    } else {  // BITS == 3
-        uint32_t prev = dpp<quad_perm(0, 0, 1, 2)>(a);            // lane i gets dword i-1
-        uint64_t w = ((uint64_t)a << 32) | prev;
-        return (w >> (32 - 8 * i)) & 0xFFFFFFull;
     }
 }
 
@@ -612,17 +555,6 @@ __device__ __forceinline__ void add_raw_bf16(const u32x4 v, float *acc)
     }
 }
 
-// Integer-path decode of code j of `v` to binary32 times 2^k (exact): the magnitude code,
-// shifted so that its mantissa sits at the top of binary32's fraction field, is
-// value * 2^(beta-127) as a (possibly subnormal) binary32; ldexp moves it to value * 2^e.
-template <class E>
-__device__ __forceinline__ float decode(uint64_t v, int j, int k /* e + 127 - beta */)
-{
-    const uint32_t c = (uint32_t)(v >> (j * E::bits));
-    const uint32_t bits = ((c & E::magmask) << (23 - E::y)) | ((c >> (E::x + E::y)) << 31);
-    return ldexpf(__uint_as_float(bits), k);
-}
-
 template <int K>
 __device__ __forceinline__ f32x2 cvt_fp4_pair(uint32_t v, float s)
 {
@@ -704,102 +636,6 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f)
     return (f != f) ? 0x7FC0u : r;
 }
 
-// RC: ranks whose loads are issued together.
-// OWN: rank a.own_rank contributes its uncompressed bf16 partial instead of a decoded one (the
-// paper's Profiling setup: a worker decompresses the N-1 partials of the other workers).
-template <class E, int B, bool OUT_BF16, int U, int RC, bool NTL, bool NTS, bool HW, bool OWN = false>
-__global__ __launch_bounds__(kThreads) void dequant_reduce_kernel(ReduceArgs a)
-{
-    constexpr int G = B / 8;
-    constexpr bool kHw = HW && E::hw != HW_NONE;
-    const int lane = (int)(threadIdx.x & 63);
-    const int wave = (int)(threadIdx.x >> 6);
-    const size_t wave_base =
-        ((size_t)blockIdx.x * (kThreads / 64) + (size_t)wave) * (size_t)(U * 64);
-    const ScaleFmt sf = a.sf;
-
-    // One wave step; `tail` (a std::bool_constant) says whether the step may touch the tensor's
-    // last, partial quad of units.  Only the last step of the last wave does, and keeping that
-    // case out of the common step keeps its loads free of branches, so they issue together.
-    auto step = [&](int u, auto tail) {
-        const size_t unit = wave_base + (size_t)(u * 64 + lane);
-        const bool valid = unit < a.units;
-        float acc[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) acc[j] = kFoldStart;
-        bool poisoned = false;                   // some rank marked this block non-finite
-        for (int r0 = 0; r0 < a.tp; r0 += RC) {
-            uint64_t v[RC];
-            int sc[RC];
-#pragma unroll
-            for (int i = 0; i < RC; ++i) {
-                const bool on = valid && (r0 + i < a.tp) && !(OWN && r0 + i == a.own_rank);
-                const int r = min(r0 + i, a.tp - 1);
-                v[i] = load_codes<E::bits, NTL, decltype(tail)::value>(
-                    (const uint32_t *)a.codes[r], unit, a.units,
-                    r0 + i < a.tp && !(OWN && r0 + i == a.own_rank));
-                if (!on)
-                    sc[i] = sf.sbias;
-                else if (sf.sbits == 8)
-                    sc[i] = (int)ld<NTL>((const uint8_t *)a.scales[r] + unit / G);
-                else
-                    sc[i] = (int)load_bits((const uint8_t *)a.scales[r], (unit / G) * (size_t)sf.sbits,
-                                           sf.sbits, (a.units / G * (size_t)sf.sbits + 7) >> 3);
-            }
-#pragma unroll
-            for (int i = 0; i < RC; ++i) {
-                if (OWN && r0 + i == a.own_rank) {
-                    const u32x4 raw = valid ? ld<NTL>((const u32x4 *)a.own_x + unit)
-                                            : u32x4{0u, 0u, 0u, 0u};
-                    add_raw_bf16(raw, acc);
-                } else if (r0 + i < a.tp) {
-                    const int e = sc[i] - sf.sbias;
-                    const bool marker = sf.has_nan && sc[i] == 255;
-                    poisoned = poisoned || marker;
-                    float d[8];
-                    // the hardware format reads the code as value * 2^(beta - hw_bias), so
-                    // multiply by 2^(e - beta + hw_bias): usable while it has an exponent field
-                    const int field = e - E::beta + E::hw_bias + 127;
-                    const bool ok = field >= 0 && field <= 254;
-                    if (kHw && __builtin_amdgcn_ballot_w64(!ok) == 0) {
-                        decode_unit_hw<E>(v[i], __uint_as_float((uint32_t)field << 23), d);
-                    } else {
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) d[j] = decode<E>(v[i], j, e + 127 - E::beta);
-                    }
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) acc[j] += d[j];
-                }
-            }
-        }
-        if (poisoned) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) acc[j] = __uint_as_float(0x7FC00000u);
-        }
-        if (valid) {
-            if (OUT_BF16) {
-                u32x4 o;
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    o[j] = f32_to_bf16_rne(acc[2 * j]) | (f32_to_bf16_rne(acc[2 * j + 1]) << 16);
-                st<NTS>((u32x4 *)a.out + unit, o);
-            } else {
-                f32x4 *o = (f32x4 *)a.out + unit * 2;
-                st<NTS>(o, f32x4{acc[0], acc[1], acc[2], acc[3]});
-                st<NTS>(o + 1, f32x4{acc[4], acc[5], acc[6], acc[7]});
-            }
-        }
-    };
-#pragma unroll 1
-    for (int u = 0; u < U; ++u) {
-        const size_t last_unit = wave_base + (size_t)(u * 64 + 63);
-        if ((a.units & 3) != 0 && last_unit >= (a.units & ~(size_t)3))
-            step(u, std::true_type{});
-        else
-            step(u, std::false_type{});
-    }
-}
-
 // LEN bits starting at bit `pos` of a little-endian stream held in NW dwords.  Callers pass
 // positions that are constants after unrolling, so this folds to one or two instructions.
 template <int NW>
@@ -833,45 +669,69 @@ struct ChunkBits {
 // Loads the lane's share of one rank's arrays for the wave tile that starts at chunk
 // `wave_chunk0`.  A lane that is not `on` (past the end, a rank beyond tp, the own rank of the OWN
 // form) loads nothing and reads as code 0 with "e = 0".  STAGED: the codes of a full wave tile
-// (`full`) are left to load_codes_staged and only the scales are loaded here.
+// (`full`) are left to load_codes_staged and only the scales are loaded here.  `tail_units` is 0
+// for a whole chunk; the tensor's last chunk holds only 1 to 3 units of 8 elements when the size
+// is not a multiple of 32 (blocks of 8 or 16), and that one lane fetches its bytes one by one so
+// that nothing past the arrays is read.  `units` is the tensor's size in units.
 template <class E, int B, bool NTL, bool STAGED = false>
 __device__ __forceinline__ void load_chunk(ChunkBits<E::bits> &c, const void *codes, const void *scales,
                                            size_t wave_chunk0, int lane, bool on, const ScaleFmt &sf,
-                                           size_t nchunks, bool full = false)
+                                           size_t units, bool full = false, int tail_units = 0)
 {
     constexpr int W = E::bits, NB = 32 / B;
     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
     const uint32_t *cp = (const uint32_t *)codes + wave_chunk0 * W + lane * W;
 #pragma unroll
     for (int k = 0; k < W; ++k) c.cw[k] = 0u;
-    if (on && !(STAGED && full)) {
-        if (W == 4) {
-            const u32x4 v = ld<NTL>((const u32x4 *)cp);
-            c.cw[0] = v.x; c.cw[1] = v.y; c.cw[2] = v.z; c.cw[3 < W ? 3 : 0] = v.w;
-        } else if (W == 6) {
-#pragma unroll
-            for (int k = 0; k < 3; ++k) {
-                const u32x2 v = ld<NTL>((const u32x2 *)cp + k);
-                c.cw[(2 * k) < W ? 2 * k : 0] = v.x;
-                c.cw[(2 * k + 1) < W ? 2 * k + 1 : 0] = v.y;
-            }
-        } else {
-#pragma unroll
-            for (int k = 0; k < W; ++k) c.cw[k] = ld<NTL>(cp + k);
-        }
-    }
     // NB scale bytes, little-endian in one register; idle lanes read as "e = 0"
     uint32_t sb = (uint32_t)sf.sbias * 0x01010101u;
-    if (on && sf.sbits == 8) {
-        const uint8_t *sp = (const uint8_t *)scales + wave_chunk0 * NB + lane * NB;
-        if (NB == 1) sb = ld<NTL>(sp);
-        else if (NB == 2) sb = ld<NTL>((const uint16_t *)sp);
-        else sb = ld<NTL>((const uint32_t *)sp);
+    if (on && tail_units) {
+        const uint8_t *bp = (const uint8_t *)cp;
+        const int nbytes = tail_units * W;       // a unit's 8 codes are W bytes
+#pragma unroll
+        for (int k = 0; k < W; ++k)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (4 * k + j < nbytes) c.cw[k] |= (uint32_t)bp[4 * k + j] << (8 * j);
+        if (sf.sbits == 8) {
+            const uint8_t *sp = (const uint8_t *)scales + wave_chunk0 * NB + lane * NB;
+            const int nscales = tail_units * 8 / B;
+            sb = 0;
+#pragma unroll
+            for (int n = 0; n < NB; ++n)
+                sb |= (n < nscales ? (uint32_t)sp[n] : (uint32_t)sf.sbias) << (8 * n);
+        }
     } else if (on) {
-        // packed stream: NB fields of s bits, re-spread to one byte each
+        if (!(STAGED && full)) {
+            if (W == 4) {
+                const u32x4 v = ld<NTL>((const u32x4 *)cp);
+                c.cw[0] = v.x; c.cw[1] = v.y; c.cw[2] = v.z; c.cw[3 < W ? 3 : 0] = v.w;
+            } else if (W == 6) {
+#pragma unroll
+                for (int k = 0; k < 3; ++k) {
+                    const u32x2 v = ld<NTL>((const u32x2 *)cp + k);
+                    c.cw[(2 * k) < W ? 2 * k : 0] = v.x;
+                    c.cw[(2 * k + 1) < W ? 2 * k + 1 : 0] = v.y;
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < W; ++k) c.cw[k] = ld<NTL>(cp + k);
+            }
+        }
+        if (sf.sbits == 8) {
+            const uint8_t *sp = (const uint8_t *)scales + wave_chunk0 * NB + lane * NB;
+            if (NB == 1) sb = ld<NTL>(sp);
+            else if (NB == 2) sb = ld<NTL>((const uint16_t *)sp);
+            else sb = ld<NTL>((const uint32_t *)sp);
+        }
+    }
+    if (on && sf.sbits < 8) {
+        // packed stream: NB fields of s bits, re-spread to one byte each (load_bits reads no
+        // byte past the stream's end; fields of blocks past the end are never used)
         const size_t chunk = wave_chunk0 + (size_t)lane;
+        const size_t nblocks = units * 8 / B;
         const uint32_t raw = load_bits((const uint8_t *)scales, chunk * NB * (size_t)sf.sbits,
-                                       NB * sf.sbits, (nchunks * NB * (size_t)sf.sbits + 7) >> 3);
+                                       NB * sf.sbits, (nblocks * (size_t)sf.sbits + 7) >> 3);
         sb = 0;
 #pragma unroll
         for (int n = 0; n < NB; ++n)
@@ -1002,10 +862,11 @@ __device__ __forceinline__ void apply_poison(float (&acc)[32], const bool (&pois
 // each touch 64 different lines.
 template <bool NTL>
 __device__ __forceinline__ void load_raw_pieces(u32x4 (&pv)[4], const void *own_x, size_t wave_chunk0,
-                                                int lane, size_t nchunks)
+                                                int lane, size_t units)
 {
     const u32x4 *src = (const u32x4 *)own_x + wave_chunk0 * 4;
-    const size_t own_pieces = wave_chunk0 < nchunks ? (nchunks - wave_chunk0) * 4 : 0;
+    // a unit's 8 bfloat16 values are one piece
+    const size_t own_pieces = wave_chunk0 * 4 < units ? units - wave_chunk0 * 4 : 0;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const int g = k * 64 + lane;             // piece index within the wave's 4 KiB
@@ -1036,7 +897,7 @@ __device__ __forceinline__ void take_raw_chunk(u32x4 *t, const u32x4 (&pv)[4], u
 // output as contiguous 1 KiB store instructions.
 template <bool OUT_BF16, bool NTS>
 __device__ __forceinline__ void store_sums(u32x4 *t, const float (&acc)[32], void *outp, size_t wave_chunk0,
-                                           int lane, size_t nchunks)
+                                           int lane, size_t units)
 {
     constexpr int OC = OUT_BF16 ? 4 : 8;         // 16-byte output pieces per lane
 #pragma unroll
@@ -1056,7 +917,8 @@ __device__ __forceinline__ void store_sums(u32x4 *t, const float (&acc)[32], voi
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     u32x4 *out = (u32x4 *)outp + wave_chunk0 * OC;
-    const size_t pieces_left = wave_chunk0 < nchunks ? (nchunks - wave_chunk0) * OC : 0;
+    // a unit's 8 sums are OC / 4 pieces; the tensor's last chunk may hold fewer than 4 units
+    const size_t pieces_left = wave_chunk0 * 4 < units ? (units - wave_chunk0 * 4) * (OC / 4) : 0;
 #pragma unroll
     for (int r = 0; r < OC; ++r) {
         const int g = r * 64 + lane;             // piece index within the tile
@@ -1302,10 +1164,12 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
     // address a 32-bit offset
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const size_t wave_chunk0 = ((size_t)blockIdx.x * (WG / 64) + (size_t)wave) * 64;
-    const size_t nchunks = a.units / 4;
+    const size_t nchunks = (a.units + 3) / 4;    // the last one may hold only 1 to 3 units
     if (wave_chunk0 >= nchunks) return;          // the whole wave
     const bool valid = wave_chunk0 + (size_t)lane < nchunks;
-    const bool full = wave_chunk0 + 64 <= nchunks;
+    const bool full = wave_chunk0 + 64 <= a.units / 4;   // 64 whole chunks
+    // units in this lane's chunk if it is the tensor's last, partial one, else 0
+    const int tail_units = (!full && wave_chunk0 + (size_t)lane == a.units / 4) ? (int)(a.units & 3) : 0;
     const ScaleFmt sf = a.sf;
     u32x4 *t = tile[kPieces > 0 ? wave : 0];
 
@@ -1319,7 +1183,7 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
     u32x4 own[4];
     if constexpr (OWN) {
         u32x4 pv[4];
-        load_raw_pieces<NTL>(pv, a.own_x, wave_chunk0, lane, nchunks);
+        load_raw_pieces<NTL>(pv, a.own_x, wave_chunk0, lane, a.units);
         take_raw_chunk(t, pv, own, lane);
     }
 
@@ -1335,7 +1199,7 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
             cptr[i] = a.codes[rr];
             // with staged code loads this fetches the scales only
             load_chunk<E, B, NTL, kStaged>(g[i], cptr[i], a.scales[rr], wave_chunk0, lane, valid && on[i], sf,
-                                           nchunks, full);
+                                           a.units, full, tail_units);
         }
         if (kStaged && !kDma && full) {
             uint32_t cw[RC][W];
@@ -1371,9 +1235,9 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
     }
     apply_poison<B>(acc, poisoned);
     if (FUSED)
-        requantize_sums<E, B, NTS, HW>(acc, a.codes_out, a.scales_out, wave_chunk0, lane, nchunks, sf);
+        requantize_sums<E, B, NTS, HW>(acc, a.codes_out, a.scales_out, wave_chunk0, lane, a.units / 4, sf);
     else
-        store_sums<OUT_BF16, NTS>(t, acc, a.out, wave_chunk0, lane, nchunks);
+        store_sums<OUT_BF16, NTS>(t, acc, a.out, wave_chunk0, lane, a.units);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -242,11 +242,13 @@ def test_reduce_config1_all_formats(mxc, oracle_mod, x, y, B):
 
 
 def test_reduce_and_fused_do_not_write_past_the_end(mxc, oracle_mod):
-    """Canaries behind every output of the reduce kernels (f32, bf16, own-raw, fused, and the
-    unit form used for sizes that are not a multiple of 32), on ragged sizes."""
+    """Canaries behind every output of the reduce kernels (f32, bf16, own-raw, fused), on ragged
+    sizes, among them sizes that are not a multiple of 32 elements: their last chunk holds 8, 16
+    or 24 elements, alone in a wave tile or behind whole tiles."""
     rng = np.random.default_rng(4)
     for (x, y, B, T, H) in ((2, 1, 32, 3, 96), (2, 2, 32, 5, 2080), (3, 2, 32, 1, 32), (2, 1, 8, 3, 40),
-                            (3, 2, 16, 7, 48), (1, 1, 8, 1, 8)):
+                            (3, 2, 16, 7, 48), (1, 1, 8, 1, 8), (2, 2, 8, 5, 1048), (2, 1, 16, 129, 80),
+                            (3, 2, 8, 3, 2056)):
         fo, fg = oracle_mod.Format(x, y, B, 8), mxc.Format(x, y, B, 8)
         tp = 3
         ocs = [rng.integers(0, 2 ** fo.bits, size=(T, H), dtype=np.uint8) for _ in range(tp)]
