@@ -895,7 +895,7 @@ __device__ __forceinline__ void take_raw_chunk(u32x4 *t, const u32x4 (&pv)[4], u
 // of the wave's tile; piece c is written to slot (c + l) % OC of the lane's row so that both the
 // row-wise writes and the piece-wise reads spread over all banks.  The wave then writes its
 // output as contiguous 1 KiB store instructions.
-template <bool OUT_BF16, bool NTS>
+template <bool OUT_BF16, bool NTS, bool FULL = false>
 __device__ __forceinline__ void store_sums(u32x4 *t, const float (&acc)[32], void *outp, size_t wave_chunk0,
                                            int lane, size_t units)
 {
@@ -924,7 +924,7 @@ __device__ __forceinline__ void store_sums(u32x4 *t, const float (&acc)[32], voi
         const int g = r * 64 + lane;             // piece index within the tile
         const int l = g / OC, c = g % OC;
         const u32x4 v = t[l * OC + ((c + l) & (OC - 1))];
-        if ((size_t)g < pieces_left) st<NTS>(out + g, v);
+        if (FULL || (size_t)g < pieces_left) st<NTS>(out + g, v);
     }
 }
 
@@ -932,7 +932,7 @@ __device__ __forceinline__ void store_sums(u32x4 *t, const float (&acc)[32], voi
 // input) and stores codes and scales.  The lane holds whole blocks, so block maximum, scale and
 // codes need no other lane.  Every lane of the wave must call this (narrow scales are gathered
 // across the wave).
-template <class E, int B, bool NTS, bool HW>
+template <class E, int B, bool NTS, bool HW, bool FULL = false>
 __device__ __forceinline__ void requantize_sums(const float (&acc)[32], void *codes_out, void *scales_out,
                                                 size_t wave_chunk0, int lane, size_t nchunks,
                                                 const ScaleFmt &sf)
@@ -940,7 +940,7 @@ __device__ __forceinline__ void requantize_sums(const float (&acc)[32], void *co
     constexpr int W = E::bits, NB = 32 / B;
     constexpr bool kHw = HW && E::hw != HW_NONE;
     constexpr bool kChunkBf6 = E::x == 3 && E::y == 2 && B == 32;
-    const bool valid = wave_chunk0 + (size_t)lane < nchunks;
+    const bool valid = FULL || wave_chunk0 + (size_t)lane < nchunks;
     uint32_t cw[W];
 #pragma unroll
     for (int k = 0; k < W; ++k) cw[k] = 0u;
@@ -1132,46 +1132,30 @@ __device__ __forceinline__ void read_codes_from_lds(uint32_t (&cw)[W], const u32
     }
 }
 
-// The kernel: one wave per wave tile, no workgroup barrier.
+// One wave tile: decode and add the tp ranks' chunks, then write (or re-quantize) the sums.
 //
-// RC: ranks whose loads are issued together.  FUSED: instead of storing the sums, quantize them
-// again in the lane that holds them and store codes and scales; bit-identical to running the
-// unfused kernels one after the other.  OWN: rank a.own_rank contributes its uncompressed bf16
-// partial.  STAGED: 3-, 5- and 6-bit codes are loaded as contiguous 16-byte pieces and
-// redistributed through LDS (load_codes_staged).  WG: threads per workgroup (a multiple of 64).
-template <class E, int B, bool OUT_BF16, int RC, bool NTL, bool NTS, bool HW, bool FUSED = false,
-          bool OWN = false, int WG = kThreads, int STAGE = 0>
-__global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
+// FAST = the common case, compiled without anything it does not need: the tile is 64 whole chunks
+// (every tile but a tensor's last is), tp <= kFastRanks so that the rank loop unrolls over fixed
+// indices (the ranks' pointers then arrive with the other kernel arguments instead of one
+// dependent scalar load per rank), and the scale format is fixed by S8 (true: one byte per block;
+// false: a narrower bit stream).  The other instance (FAST = false) takes whatever is left — a
+// partial last tile, the 1 to 3 unit chunk that ends a tensor whose size is not a multiple of 32,
+// more ranks — with each lane loading its own dwords under bounds checks, two ranks at a time.
+constexpr int kFastRanks = 8;
+
+template <class E, int B, bool OUT_BF16, int RC, bool NTL, bool NTS, bool HW, bool FUSED, bool OWN, int STAGE,
+          bool FAST, bool S8>
+__device__ __forceinline__ void reduce_wave_tile(const ReduceArgs &a, u32x4 *t, size_t wave_chunk0, int lane)
 {
-    static_assert(!(FUSED && OWN), "the fused form has no own-raw variant");
     constexpr int NB = 32 / B;                   // blocks (scales) per chunk
     constexpr int W = E::bits;                   // dwords of codes per chunk
-    constexpr int OC = OUT_BF16 ? 4 : 8;         // 16-byte output pieces per lane
-    constexpr bool kStaged = STAGE != 0 && W != 4;
+    constexpr bool kStaged = FAST && (STAGE == 2 || (STAGE == 1 && W != 4));
     constexpr bool kDma = kStaged && STAGE == 2;
-    // LDS per wave, in 16-byte pieces: the output exchange, the staging of code pieces and the
-    // own rank's raw pieces use the same area one after the other
-    constexpr int kOutPieces = FUSED ? 0 : 64 * OC;
-    constexpr int kStagePieces = kStaged ? RC * 16 * W : 0;
-    constexpr int kOwnPieces = OWN ? 256 : 0;
-    constexpr int kPieces = kOutPieces > kStagePieces ? (kOutPieces > kOwnPieces ? kOutPieces : kOwnPieces)
-                                                      : (kStagePieces > kOwnPieces ? kStagePieces : kOwnPieces);
-    __shared__ u32x4 tile[WG / 64][kPieces > 0 ? kPieces : 1];
-
-    const int lane = (int)(threadIdx.x & 63);
-    // the wave index is the same in every lane: telling the compiler so keeps wave_chunk0 and
-    // every base address derived from it in scalar registers, and the per-lane part of an
-    // address a 32-bit offset
-    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const size_t wave_chunk0 = ((size_t)blockIdx.x * (WG / 64) + (size_t)wave) * 64;
     const size_t nchunks = (a.units + 3) / 4;    // the last one may hold only 1 to 3 units
-    if (wave_chunk0 >= nchunks) return;          // the whole wave
-    const bool valid = wave_chunk0 + (size_t)lane < nchunks;
-    const bool full = wave_chunk0 + 64 <= a.units / 4;   // 64 whole chunks
+    const bool valid = FAST || wave_chunk0 + (size_t)lane < nchunks;
     // units in this lane's chunk if it is the tensor's last, partial one, else 0
-    const int tail_units = (!full && wave_chunk0 + (size_t)lane == a.units / 4) ? (int)(a.units & 3) : 0;
-    const ScaleFmt sf = a.sf;
-    u32x4 *t = tile[kPieces > 0 ? wave : 0];
+    const int tail_units = (!FAST && wave_chunk0 + (size_t)lane == a.units / 4) ? (int)(a.units & 3) : 0;
+    const ScaleFmt sf = (FAST && S8) ? ScaleFmt{8, 127, 254, 255, 1} : a.sf;
 
     float acc[32];
 #pragma unroll
@@ -1187,21 +1171,34 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
         take_raw_chunk(t, pv, own, lane);
     }
 
-    for (int r0 = 0; r0 < a.tp; r0 += RC) {
+    // FAST: all rank pointers are fetched from the argument block up front, in two wide scalar
+    // loads, instead of one pair per rank right before its use
+    const void *cp_all[FAST ? kFastRanks : 1], *sp_all[FAST ? kFastRanks : 1];
+    if (FAST) {
+#pragma unroll
+        for (int r = 0; r < kFastRanks; ++r) {
+            cp_all[FAST ? r : 0] = a.codes[r];
+            sp_all[FAST ? r : 0] = a.scales[r];
+        }
+    }
+
+    // ranks r0 .. r0 + RC - 1
+    auto group = [&](int r0) {
         ChunkBits<W> g[RC];
         bool on[RC];
         const void *cptr[RC];
 #pragma unroll
         for (int i = 0; i < RC; ++i) {
             const int r = r0 + i;
-            const int rr = min(r, a.tp - 1);
+            const int rr = FAST ? r : min(r, a.tp - 1);
             on[i] = r < a.tp && !(OWN && r == a.own_rank);
-            cptr[i] = a.codes[rr];
+            cptr[i] = FAST ? cp_all[FAST ? rr : 0] : a.codes[rr];
+            const void *sptr = FAST ? sp_all[FAST ? rr : 0] : a.scales[rr];
             // with staged code loads this fetches the scales only
-            load_chunk<E, B, NTL, kStaged>(g[i], cptr[i], a.scales[rr], wave_chunk0, lane, valid && on[i], sf,
-                                           a.units, full, tail_units);
+            load_chunk<E, B, NTL, kStaged>(g[i], cptr[i], sptr, wave_chunk0, lane, valid && on[i], sf,
+                                           a.units, FAST, tail_units);
         }
-        if (kStaged && !kDma && full) {
+        if (kStaged && !kDma) {
             uint32_t cw[RC][W];
             load_codes_staged<W, RC, NTL>(cw, t, cptr, on, wave_chunk0, lane);
 #pragma unroll
@@ -1209,7 +1206,7 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
 #pragma unroll
                 for (int k = 0; k < W; ++k) g[i].cw[k] = cw[i][k];
         }
-        if (kDma && full) {
+        if (kDma) {
             request_codes_to_lds<W, RC, NTL>(t, cptr, on, wave_chunk0, lane);
             __builtin_amdgcn_s_waitcnt(0);       // every counter at zero: the pieces are in LDS
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -1223,21 +1220,71 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
                 for (int k = 0; k < 4; ++k) add_raw_bf16(own[k], acc + 8 * k);
             } else if (r0 + i < a.tp) {
                 // each rank's dwords are fetched from LDS only when its turn comes
-                if (kDma && full) read_codes_from_lds<W>(g[i].cw, t, i, lane);
+                if (kDma) read_codes_from_lds<W>(g[i].cw, t, i, lane);
                 add_chunk<E, B, HW>(g[i], sf, acc, poisoned);
             }
         }
-        if (kDma && full) {
+        if (kDma) {
             // the area is free again once every lane has read its dwords
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
         }
+    };
+    if (FAST) {
+#pragma unroll
+        for (int r0 = 0; r0 < kFastRanks; r0 += RC)
+            if (r0 < a.tp) group(r0);
+    } else {
+        for (int r0 = 0; r0 < a.tp; r0 += RC) group(r0);
     }
     apply_poison<B>(acc, poisoned);
     if (FUSED)
-        requantize_sums<E, B, NTS, HW>(acc, a.codes_out, a.scales_out, wave_chunk0, lane, a.units / 4, sf);
+        requantize_sums<E, B, NTS, HW, FAST>(acc, a.codes_out, a.scales_out, wave_chunk0, lane, a.units / 4, sf);
     else
-        store_sums<OUT_BF16, NTS>(t, acc, a.out, wave_chunk0, lane, a.units);
+        store_sums<OUT_BF16, NTS, FAST>(t, acc, a.out, wave_chunk0, lane, a.units);
+}
+
+// The kernel: one wave per wave tile, no workgroup barrier.
+//
+// RC: ranks whose loads are issued together (a divisor of kFastRanks).  FUSED: instead of storing
+// the sums, quantize them again in the lane that holds them and store codes and scales;
+// bit-identical to running the unfused kernels one after the other.  OWN: rank a.own_rank
+// contributes its uncompressed bf16 partial.  STAGE: how the codes of a full tile are fetched: 0 =
+// each lane loads its own dwords; 1 = contiguous 16-byte pieces redistributed through LDS
+// (load_codes_staged; 3-, 5- and 6-bit codes); 2 = the same with loads that write LDS directly
+// (request_codes_to_lds; any width).  WG: threads per workgroup (a multiple of 64).
+template <class E, int B, bool OUT_BF16, int RC, bool NTL, bool NTS, bool HW, bool FUSED = false,
+          bool OWN = false, int WG = kThreads, int STAGE = 0>
+__global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
+{
+    static_assert(!(FUSED && OWN), "the fused form has no own-raw variant");
+    static_assert(kFastRanks % RC == 0, "RC must divide kFastRanks");
+    constexpr int W = E::bits;
+    constexpr int OC = OUT_BF16 ? 4 : 8;         // 16-byte output pieces per lane
+    // LDS per wave, in 16-byte pieces: the output exchange, the staging of code pieces and the
+    // own rank's raw pieces use the same area one after the other
+    constexpr int kOutPieces = FUSED ? 0 : 64 * OC;
+    constexpr int kStagePieces = (STAGE == 2 || (STAGE == 1 && W != 4)) ? RC * 16 * W : 0;
+    constexpr int kOwnPieces = OWN ? 256 : 0;
+    constexpr int kPieces = kOutPieces > kStagePieces ? (kOutPieces > kOwnPieces ? kOutPieces : kOwnPieces)
+                                                      : (kStagePieces > kOwnPieces ? kStagePieces : kOwnPieces);
+    __shared__ u32x4 tile[WG / 64][kPieces > 0 ? kPieces : 1];
+
+    const int lane = (int)(threadIdx.x & 63);
+    // the wave index is the same in every lane: telling the compiler so keeps wave_chunk0 and
+    // every base address derived from it in scalar registers, and the per-lane part of an
+    // address a 32-bit offset
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const size_t wave_chunk0 = ((size_t)blockIdx.x * (WG / 64) + (size_t)wave) * 64;
+    if (wave_chunk0 * 4 >= a.units) return;      // the whole wave
+    u32x4 *t = tile[kPieces > 0 ? wave : 0];
+    const bool fast = wave_chunk0 + 64 <= a.units / 4 && a.tp <= kFastRanks;
+    if (fast && a.sf.sbits == 8)
+        reduce_wave_tile<E, B, OUT_BF16, RC, NTL, NTS, HW, FUSED, OWN, STAGE, true, true>(a, t, wave_chunk0, lane);
+    else if (fast)
+        reduce_wave_tile<E, B, OUT_BF16, RC, NTL, NTS, HW, FUSED, OWN, STAGE, true, false>(a, t, wave_chunk0, lane);
+    else
+        reduce_wave_tile<E, B, OUT_BF16, (RC > 2 ? 2 : RC), NTL, NTS, HW, FUSED, OWN, 0, false, false>(a, t, wave_chunk0, lane);
 }
 
 // ---------------------------------------------------------------------------------------------
