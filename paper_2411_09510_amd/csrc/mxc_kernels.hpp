@@ -13,8 +13,10 @@
 // element format maps onto a hardware format bit for bit (checked exhaustively against the CPU
 // oracle): E2M1 is the hardware FP4; a format with 2 (3) mantissa bits is the low part of the
 // code space of BF8 = E5M2 (FP8 = E4M3) once the block scale is shifted so that the smallest
-// normals coincide.  Everything else, and every block whose scale leaves the range in which that
-// shift is representable, takes the integer path below, which is exact for every input.
+// normals coincide; for decoding, a block of 32 E3M2 codes is one hardware BF6 block and a block
+// of 32 E2M3 or (widened by one zero bit per code) E2M2 codes one hardware FP6 block.  Everything
+// else, and every block whose scale leaves the range in which that shift is representable, takes
+// the integer path below, which is exact for every input.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -526,7 +528,7 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantArgs a)
 }
 
 // ---------------------------------------------------------------------------------------------
-// Dequantize + reduce (Profiling: decompress the gathered partials, then a plain sum).
+// Arguments and decoding helpers of the dequantize + reduce kernel.
 
 struct ReduceArgs {
     const void *codes[32];
@@ -649,14 +651,18 @@ __device__ __forceinline__ uint32_t stream_bits_rt(const uint32_t (&s)[NW], int 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Dequantize + reduce, tile form: the fast path for tensors whose size is a multiple of 32.
+// Dequantize + reduce (Profiling: decompress the gathered partials, then a plain sum).
 //
 // Each lane owns a "chunk" of 32 consecutive elements (one block of 32, two of 16, four of 8): its
-// codes are 4b contiguous bytes per rank (a single 128-bit load for 4-bit codes), its scales 1, 2
-// or 4 contiguous bytes per rank, so every load instruction of the wave is contiguous and as wide
-// as the format allows.  The lane's 32 sums are then exchanged through a wave-private LDS tile so
-// that the wave writes its 8 KiB (4 KiB for bf16) of output as contiguous 128-bit stores.  A wave
-// tile is the 64 chunks of one wave.
+// codes are 4b contiguous bytes per rank, its scales 1, 2 or 4 contiguous bytes per rank.  A wave
+// tile is the 64 chunks of one wave: per rank 16*b contiguous 16-byte pieces of codes.  4-bit
+// codes are one 128-bit load per lane; 3-, 5- and 6-bit codes, whose per-lane dwords are 12, 20
+// or 24 bytes apart, are fetched as the tile's contiguous pieces and redistributed through LDS
+// (each load instruction then asks the memory system for whole 128-byte lines; per-lane dword
+// loads ask for 64-byte halves and run 5 to 8 % slower).  The lane's 32 sums are exchanged
+// through the same wave-private LDS area so that the wave writes its 8 KiB (4 KiB for bf16) of
+// output as contiguous 128-bit stores.  A tensor's last chunk may hold only 8, 16 or 24 elements
+// (blocks of 8 or 16).
 
 // What a lane fetches for one rank of its chunk: W dwords of codes and the chunk's scale codes,
 // one per byte.
