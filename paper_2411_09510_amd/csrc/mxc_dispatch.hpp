@@ -33,8 +33,8 @@ struct TileShape {
 constexpr TileShape tile_shape(int code_bits, bool out_bf16, bool fused, bool own)
 {
     if (code_bits == 4) return own ? TileShape{8, 2} : TileShape{8, 0};
-    if (code_bits == 5) return own ? TileShape{4, 2} : (out_bf16 || fused) ? TileShape{8, 2} : TileShape{2, 2};
-    if (code_bits == 6) return fused ? TileShape{4, 2} : TileShape{8, 2};
+    if (code_bits == 5) return own ? TileShape{8, 0} : (out_bf16 || fused) ? TileShape{8, 2} : TileShape{2, 2};
+    if (code_bits == 6) return (fused || own) ? TileShape{4, 2} : TileShape{8, 2};
     return {4, 2};
 }
 constexpr int kCopyU = 1;

@@ -897,6 +897,20 @@ __device__ __forceinline__ void take_raw_chunk(u32x4 *t, const u32x4 (&pv)[4], u
     __builtin_amdgcn_wave_barrier();
 }
 
+// The same for a full wave tile with loads that write LDS directly: the 256 pieces are requested
+// here into `traw` (4 KiB); once the wave's vector-memory counter has reached zero, lane l finds
+// its four pieces at traw[4 l .. 4 l + 3].
+template <bool NTL>
+__device__ __forceinline__ void request_raw_to_lds(u32x4 *traw, const void *own_x, size_t wave_chunk0, int lane)
+{
+    typedef const void __attribute__((address_space(1))) *gptr;
+    typedef void __attribute__((address_space(3))) *lptr;
+    const u32x4 *src = (const u32x4 *)own_x + wave_chunk0 * 4;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+        __builtin_amdgcn_global_load_lds((gptr)(src + k * 64 + lane), (lptr)(traw + k * 64), 16, 0, NTL ? 2 : 0);
+}
+
 // Writes the wave tile's sums.  Exchange through LDS: lane l owns output pieces l*OC .. l*OC+OC-1
 // of the wave's tile; piece c is written to slot (c + l) % OC of the lane's row so that both the
 // row-wise writes and the piece-wise reads spread over all banks.  The wave then writes its
@@ -1151,7 +1165,8 @@ constexpr int kFastRanks = 8;
 
 template <class E, int B, bool OUT_BF16, int RC, bool NTL, bool NTS, bool HW, bool FUSED, bool OWN, int STAGE,
           bool FAST, bool S8>
-__device__ __forceinline__ void reduce_wave_tile(const ReduceArgs &a, u32x4 *t, size_t wave_chunk0, int lane)
+__device__ __forceinline__ void reduce_wave_tile(const ReduceArgs &a, u32x4 *t, int raw_offset, size_t wave_chunk0,
+                                                 int lane)
 {
     constexpr int NB = 32 / B;                   // blocks (scales) per chunk
     constexpr int W = E::bits;                   // dwords of codes per chunk
@@ -1170,11 +1185,20 @@ __device__ __forceinline__ void reduce_wave_tile(const ReduceArgs &a, u32x4 *t, 
 #pragma unroll
     for (int n = 0; n < NB; ++n) poisoned[n] = false;
 
+    // OWN: the fast instance has the raw pieces written straight into their own LDS area (behind
+    // the staging / exchange area) and reads them when the own rank's turn comes; the general one
+    // takes them through registers up front
+    constexpr bool kRawDma = OWN && FAST;
+    u32x4 *traw = t + raw_offset;
     u32x4 own[4];
     if constexpr (OWN) {
-        u32x4 pv[4];
-        load_raw_pieces<NTL>(pv, a.own_x, wave_chunk0, lane, a.units);
-        take_raw_chunk(t, pv, own, lane);
+        if (kRawDma) {
+            request_raw_to_lds<NTL>(traw, a.own_x, wave_chunk0, lane);
+        } else {
+            u32x4 pv[4];
+            load_raw_pieces<NTL>(pv, a.own_x, wave_chunk0, lane, a.units);
+            take_raw_chunk(t, pv, own, lane);
+        }
     }
 
     // FAST: all rank pointers are fetched from the argument block up front, in two wide scalar
@@ -1222,6 +1246,16 @@ __device__ __forceinline__ void reduce_wave_tile(const ReduceArgs &a, u32x4 *t, 
 #pragma unroll
         for (int i = 0; i < RC; ++i) {
             if (OWN && r0 + i == a.own_rank) {
+                if (kRawDma) {
+                    if (!kDma) {                 // no group has waited for the counters yet
+                        __builtin_amdgcn_s_waitcnt(0);
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    }
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) own[k] = traw[lane * 4 + k];
+                }
 #pragma unroll
                 for (int k = 0; k < 4; ++k) add_raw_bf16(own[k], acc + 8 * k);
             } else if (r0 + i < a.tp) {
@@ -1271,9 +1305,11 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
     // own rank's raw pieces use the same area one after the other
     constexpr int kOutPieces = FUSED ? 0 : 64 * OC;
     constexpr int kStagePieces = (STAGE == 2 || (STAGE == 1 && W != 4)) ? RC * 16 * W : 0;
-    constexpr int kOwnPieces = OWN ? 256 : 0;
-    constexpr int kPieces = kOutPieces > kStagePieces ? (kOutPieces > kOwnPieces ? kOutPieces : kOwnPieces)
-                                                      : (kStagePieces > kOwnPieces ? kStagePieces : kOwnPieces);
+    constexpr int kMainPieces = kOutPieces > kStagePieces ? kOutPieces : kStagePieces;
+    // OWN: the raw pieces get 256 more behind it (the general instance, which passes them
+    // through the main area, needs at least as many there)
+    constexpr int kPieces = OWN ? (kMainPieces > 256 ? kMainPieces : 256) + 256 : kMainPieces;
+    constexpr int kRawOffset = OWN ? kPieces - 256 : 0;
     __shared__ u32x4 tile[WG / 64][kPieces > 0 ? kPieces : 1];
 
     const int lane = (int)(threadIdx.x & 63);
@@ -1286,11 +1322,12 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
     u32x4 *t = tile[kPieces > 0 ? wave : 0];
     const bool fast = wave_chunk0 + 64 <= a.units / 4 && a.tp <= kFastRanks;
     if (fast && a.sf.sbits == 8)
-        reduce_wave_tile<E, B, OUT_BF16, RC, NTL, NTS, HW, FUSED, OWN, STAGE, true, true>(a, t, wave_chunk0, lane);
+        reduce_wave_tile<E, B, OUT_BF16, RC, NTL, NTS, HW, FUSED, OWN, STAGE, true, true>(a, t, kRawOffset, wave_chunk0, lane);
     else if (fast)
-        reduce_wave_tile<E, B, OUT_BF16, RC, NTL, NTS, HW, FUSED, OWN, STAGE, true, false>(a, t, wave_chunk0, lane);
+        reduce_wave_tile<E, B, OUT_BF16, RC, NTL, NTS, HW, FUSED, OWN, STAGE, true, false>(a, t, kRawOffset, wave_chunk0, lane);
     else
-        reduce_wave_tile<E, B, OUT_BF16, (RC > 2 ? 2 : RC), NTL, NTS, HW, FUSED, OWN, 0, false, false>(a, t, wave_chunk0, lane);
+        reduce_wave_tile<E, B, OUT_BF16, (RC > 2 ? 2 : RC), NTL, NTS, HW, FUSED, OWN, 0, false, false>(a, t, kRawOffset, wave_chunk0,
+                                                                                               lane);
 }
 
 // ---------------------------------------------------------------------------------------------
