@@ -679,7 +679,11 @@ struct ChunkBits {
 // for a whole chunk; the tensor's last chunk holds only 1 to 3 units of 8 elements when the size
 // is not a multiple of 32 (blocks of 8 or 16), and that one lane fetches its bytes one by one so
 // that nothing past the arrays is read.  `units` is the tensor's size in units.
-template <class E, int B, bool NTL, bool STAGED = false>
+// COOP (full tiles with a narrow scale format only): the tile's 64 * NB scale fields are a
+// byte-aligned run of 8 * NB * s bytes of the stream; the wave fetches it as dwords, one per lane,
+// and c.sw receives this lane's raw dword, from which spread_scale_fields later gives every
+// lane its own fields (one load per rank instead of up to five byte loads per lane).
+template <class E, int B, bool NTL, bool STAGED = false, bool COOP = false>
 __device__ __forceinline__ void load_chunk(ChunkBits<E::bits> &c, const void *codes, const void *scales,
                                            size_t wave_chunk0, int lane, bool on, const ScaleFmt &sf,
                                            size_t units, bool full = false, int tail_units = 0)
@@ -731,7 +735,10 @@ __device__ __forceinline__ void load_chunk(ChunkBits<E::bits> &c, const void *co
             else sb = ld<NTL>((const uint32_t *)sp);
         }
     }
-    if (on && sf.sbits < 8) {
+    if (COOP) {
+        const uint32_t *sp = (const uint32_t *)((const uint8_t *)scales + ((wave_chunk0 * NB * (size_t)sf.sbits) >> 3));
+        sb = (on && lane < 2 * NB * sf.sbits) ? ld<NTL>(sp + lane) : 0u;
+    } else if (on && sf.sbits < 8) {
         // packed stream: NB fields of s bits, re-spread to one byte each (load_bits reads no
         // byte past the stream's end; fields of blocks past the end are never used)
         const size_t chunk = wave_chunk0 + (size_t)lane;
@@ -744,6 +751,23 @@ __device__ __forceinline__ void load_chunk(ChunkBits<E::bits> &c, const void *co
             sb |= ((raw >> (n * sf.sbits)) & ((1u << sf.sbits) - 1u)) << (8 * n);
     }
     c.sw = sb;
+}
+
+// Second half of the cooperative scale load: `raw` is the dword this lane fetched of the tile's
+// scale-field run (lane k holds dword k).  Returns the lane's own NB fields, one per byte.  Every
+// lane of the wave must call this.
+template <int NB>
+__device__ __forceinline__ uint32_t spread_scale_fields(uint32_t raw, int lane, int sbits)
+{
+    const int pos = lane * NB * sbits;           // first bit of this lane's fields
+    const int d0 = pos >> 5;
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_ds_bpermute(4 * d0, (int)raw);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_ds_bpermute(4 * min(d0 + 1, 63), (int)raw);
+    const uint32_t bits = (uint32_t)((((uint64_t)hi << 32) | lo) >> (pos & 31));
+    uint32_t sb = 0;
+#pragma unroll
+    for (int n = 0; n < NB; ++n) sb |= ((bits >> (n * sbits)) & ((1u << sbits) - 1u)) << (8 * n);
+    return sb;
 }
 
 // 32 five-bit codes (5 dwords of the bit stream) -> 32 six-bit slots (6 dwords), slot = code << 1.
@@ -1172,6 +1196,7 @@ __device__ __forceinline__ void reduce_wave_tile(const ReduceArgs &a, u32x4 *t, 
     constexpr int W = E::bits;                   // dwords of codes per chunk
     constexpr bool kStaged = FAST && (STAGE == 2 || (STAGE == 1 && W != 4));
     constexpr bool kDma = kStaged && STAGE == 2;
+    constexpr bool kCoopScales = FAST && !S8;    // narrow scales of a full tile: one load per rank
     const size_t nchunks = (a.units + 3) / 4;    // the last one may hold only 1 to 3 units
     const bool valid = FAST || wave_chunk0 + (size_t)lane < nchunks;
     // units in this lane's chunk if it is the tensor's last, partial one, else 0
@@ -1225,8 +1250,8 @@ __device__ __forceinline__ void reduce_wave_tile(const ReduceArgs &a, u32x4 *t, 
             cptr[i] = FAST ? cp_all[FAST ? rr : 0] : a.codes[rr];
             const void *sptr = FAST ? sp_all[FAST ? rr : 0] : a.scales[rr];
             // with staged code loads this fetches the scales only
-            load_chunk<E, B, NTL, kStaged>(g[i], cptr[i], sptr, wave_chunk0, lane, valid && on[i], sf,
-                                           a.units, FAST, tail_units);
+            load_chunk<E, B, NTL, kStaged, kCoopScales>(g[i], cptr[i], sptr, wave_chunk0, lane, valid && on[i], sf,
+                                                        a.units, FAST, tail_units);
         }
         if (kStaged && !kDma) {
             uint32_t cw[RC][W];
@@ -1261,6 +1286,7 @@ __device__ __forceinline__ void reduce_wave_tile(const ReduceArgs &a, u32x4 *t, 
             } else if (r0 + i < a.tp) {
                 // each rank's dwords are fetched from LDS only when its turn comes
                 if (kDma) read_codes_from_lds<W>(g[i].cw, t, i, lane);
+                if (kCoopScales) g[i].sw = spread_scale_fields<NB>(g[i].sw, lane, sf.sbits);
                 add_chunk<E, B, HW>(g[i], sf, acc, poisoned);
             }
         }

@@ -375,11 +375,19 @@ def test_reduce_with_own_raw_partial(mxc, oracle_mod, x, y, B):
 
 @pytest.mark.parametrize("s", [4, 5, 6, 7])
 def test_reduce_narrow_scale_formats(mxc, oracle_mod, s):
-    w = workloads.small_like(workloads.CONFIGS[2], 16, 512)
-    for (x, y) in HOT:
-        fo, fg = oracle_mod.Format(x, y, 32, s), mxc.Format(x, y, 32, s)
+    """Scale streams of 4 to 7 bits per block, for blocks of 32, 16 and 8 (1, 2 and 4 fields per
+    lane), on whole wave tiles plus a partial one, in every form of the reduction."""
+    w = workloads.small_like(workloads.CONFIGS[2], 19, 544)
+    for (x, y, B) in [(x, y, 32) for (x, y) in HOT] + [(2, 1, 16), (2, 2, 8), (1, 1, 8)]:
+        fo, fg = oracle_mod.Format(x, y, B, s), mxc.Format(x, y, B, s)
         cs, ss = oracle_partials(oracle_mod, fo, w)
         check_reduce(mxc, oracle_mod, fo, fg, cs, ss, w.tokens, w.hidden)
+        packed = [torch.from_numpy(oracle_mod.pack(fo, c)).cuda() for c in cs]
+        scales = [dev_scales(oracle_mod, fo, v) for v in ss]
+        own_bits = workloads.partial_bf16(w, 2)
+        own = mxc.dequant_reduce_own(fg, 2, dev_bf16(own_bits), packed, scales)
+        torch.cuda.synchronize()
+        assert same_f32(host(own), oracle_mod.dequant_reduce_own(fo, 2, own_bits, cs, ss))
 
 
 # ------------------------------------------------------------------------ requantize --------
@@ -444,7 +452,7 @@ def test_fused_reduce_requantize_equals_unfused_pair(mxc, oracle_mod, x, y, B):
 def test_fused_and_requantize_with_narrow_scales(mxc, oracle_mod, s):
     """Narrow scale formats clamp at both ends (sums far above the range saturate, far below
     round to zero) and travel as an s-bit stream, in the fused form and in requantize alike;
-    shapes with whole wave tiles, with a ragged tail, and one that takes the unit-form reduce."""
+    shapes with whole wave tiles, with a ragged tail, and one whose size is not a multiple of 32."""
     rng = np.random.default_rng(s)
     for (x, y, B, T, H, tp) in ((3, 2, 32, 8, 1024, 4), (2, 1, 32, 3, 2080, 3), (2, 2, 16, 5, 1040, 2),
                                 (2, 1, 8, 9, 1032, 2), (1, 1, 8, 1, 40, 3)):
