@@ -67,9 +67,9 @@ def parse_format(s):
 
 
 def packed_bytes(fmt, tokens, hidden):
-    """Code bytes + scale bytes of one [tokens x hidden] tensor (8-bit scales)."""
+    """Code bytes + scale bytes of one [tokens x hidden] tensor."""
     n = tokens * hidden
-    return n * fmt.bits / 8 + n / fmt.block
+    return n * fmt.bits / 8 + n / fmt.block * fmt.scale_bits / 8
 
 
 def algorithmic_bytes(fmt, tp, tokens, hidden):
@@ -483,6 +483,34 @@ def main():
             sweep[f"e{fx}m{fy}_b{fb}"] = entry
             del ps, ql, dl, dl16, rl, wl, fl, fw, cc, sc, cw, sw
         del exact
+        # the scale format the paper recommends (Model Evaluation / appendix ablation: E5M0; Table 1
+        # is computed with it): same kernels, scales travelling as a 5-bit stream
+        for (fx, fy, fb) in ((2, 1, 32), (2, 1, 8)):
+            f = mxc.Format(fx, fy, fb, 5)
+            cb5, sb5 = mxc.packed_sizes(f, T, H)
+            ps = []
+            for _ in range(R):
+                buf = torch.empty(N * (cb5 + sb5 + 16), dtype=torch.uint8, device="cuda")
+                st = cb5 + sb5 + (-(cb5 + sb5)) % 16
+                ps.append(([buf[r * st: r * st + cb5].view(T, cb5 // T) for r in range(N)],
+                           [buf[r * st + cb5: r * st + cb5 + sb5] for r in range(N)]))
+            for i in range(R):
+                mxc.quantize_batched(f, x_sets[0], *ps[i])
+            pk = packed_bytes(f, T, H)
+            ql = [mxc.prepare_quantize_batched(f, x_sets[i % 2], *ps[i % R]) for i in range(PERIOD)]
+            dl = [mxc.prepare_dequant_reduce(f, *ps[(i + 1) % R], T, H, outs[i % NOUT]) for i in range(PERIOD)]
+            sweep[f"e{fx}m{fy}_b{fb}_e5m0_scale"] = {
+                "effective_bits": mxc.effective_bits(f), "compression_ratio": 16 / mxc.effective_bits(f),
+                "quantize": {"kernel": QUANTIZE_KERNEL, **rate(N * (T * H * 2 + pk), timer.each(lambda i: ql[i % PERIOD]()))},
+                "dequant_reduce": {"kernel": REDUCE_KERNEL, **rate(N * pk + T * H * 4, timer.each(lambda i: dl[i % PERIOD]()))},
+            }
+            del ps, ql, dl
+        # what a launch costs whatever it does: the plain copy kernel on 1 MiB
+        small_src = torch.zeros(4 << 20, dtype=torch.uint8, device="cuda")
+        small_dst = torch.zeros(4 << 20, dtype=torch.uint8, device="cuda")
+        sweep["launch_floor_copy_1MiB_kernel_us"] = float(np.mean(timer.each(
+            lambda i: mxc.copy_probe(small_dst[(i % 4) << 20:((i % 4) + 1) << 20],
+                                     small_src[(i % 4) << 20:((i % 4) + 1) << 20])))) * 1e3
         # the paper's own profiled input sizes are a few hundred tokens (Table 3: 2x64 ... 16x256):
         # one rank's quantize and the N-way reduce at 256 tokens, where a call is launch-bound
         f = mxc.Format(2, 1, 32, 8)
