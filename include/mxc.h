@@ -157,8 +157,8 @@ int mxc_dequant_reduce_requantize(const mxc_format *fmt, int tp, const void *con
                                   void *codes_out, void *scales_out, void *hip_stream);
 
 /* Measurement aid: copy `bytes` (a multiple of 16, both pointers 16-byte aligned) from src to
- * dst on the device with 128-bit loads and stores.  Its rate is the practical ceiling the
- * codec kernels are compared with. */
+ * dst on the device with nontemporal 128-bit loads and stores, one per lane.  Its rate is the
+ * practical ceiling the codec kernels are compared with. */
 int mxc_copy_probe(void *dst, const void *src, size_t bytes, void *hip_stream);
 
 /* Measurement aid: arm a pair of HIP events (hipEvent_t passed as void*, created by the caller with

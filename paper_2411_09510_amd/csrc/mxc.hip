@@ -252,7 +252,7 @@ int mxc_copy_probe(void *dst, const void *src, size_t bytes, void *hip_stream)
     if (!aligned(dst, 16) || !aligned(src, 16)) return MXC_ERR_ALIGN;
     if (bytes == 0) return empty_ok();
     const size_t n16 = bytes / 16;
-    return launch(copy_kernel<kCopyU, false>, dim3(grid_for(n16, kCopyU)), (hipStream_t)hip_stream,
+    return launch(copy_kernel<kCopyU, true>, dim3(grid_for(n16, kCopyU)), (hipStream_t)hip_stream,
                   (u32x4 *)dst, (const u32x4 *)src, n16);
 }
 

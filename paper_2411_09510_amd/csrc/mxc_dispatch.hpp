@@ -37,6 +37,8 @@ constexpr TileShape tile_shape(int code_bits, bool out_bf16, bool fused, bool ow
     if (code_bits == 6) return (fused || own) ? TileShape{4, 2} : TileShape{8, 2};
     return {4, 2};
 }
+// the copy probe: one 16-byte piece per lane, nontemporal (measured: 0.81 of peak against 0.77 with
+// plain loads and stores, and against 0.67-0.77 for every form that moves more per wave)
 constexpr int kCopyU = 1;
 constexpr bool kHw = true;          // use the scaled-conversion instructions where exact
 
