@@ -53,6 +53,8 @@ def parse_args():
     ap.add_argument("--no-sweep", action="store_true", help="skip the untimed sweep")
     ap.add_argument("--no-pipelines", action="store_true",
                     help="skip the requantize pipelines of configurations 4 and 5 in the sweep")
+    ap.add_argument("--tp-sweep", action="store_true",
+                    help="add the reduce kernel's rate from 1, 2, 4, ... of the partials to the sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--quality-table", action="store_true",
                     help="add the quality proxy (SQNR of the reduced output) for every element "
@@ -505,6 +507,22 @@ def main():
                 "dequant_reduce": {"kernel": REDUCE_KERNEL, **rate(N * pk + T * H * 4, timer.each(lambda i: dl[i % PERIOD]()))},
             }
             del ps, ql, dl
+        # how the reduce kernel's rate depends on the number of input streams: the same output
+        # (float32 [T x H]) from 1, 2, 4 and all N partials
+        if args.tp_sweep:
+            f = mxc.Format(*w.formats[0])
+            ps = [packed_set(f) for _ in range(R)]
+            for i in range(R):
+                mxc.quantize_batched(f, x_sets[0], *ps[i])
+            pk = packed_bytes(f, T, H)
+            by_tp = {}
+            for tpn in sorted({1, 2, max(N // 2, 1), N}):
+                dl = [mxc.prepare_dequant_reduce(f, ps[i % R][0][:tpn], ps[i % R][1][:tpn], T, H, outs[i % NOUT])
+                      for i in range(PERIOD)]
+                by_tp["tp%d" % tpn] = rate(tpn * pk + T * H * 4, timer.each(lambda i: dl[i % PERIOD]()))
+                del dl
+            sweep["dequant_reduce_by_number_of_partials_e%dm%d" % (f.ebits, f.mbits)] = by_tp
+            del ps
         # what a launch costs whatever it does: the plain copy kernel on 1 MiB
         small_src = torch.zeros(4 << 20, dtype=torch.uint8, device="cuda")
         small_dst = torch.zeros(4 << 20, dtype=torch.uint8, device="cuda")
