@@ -850,22 +850,21 @@ def test_tensor_beyond_two_to_the_32_elements(mxc, oracle_mod, x, y):
 
 # ------------------------------------------------------------------------ random cases ------
 
-def random_cases(count, seed):
+def random_cases(count, seed, tp_max=9, t_max=39, h_blocks=69):
     rng = np.random.default_rng(seed)
     cases = []
     for k in range(count):
         x, y = ALL_ELEMENTS[rng.integers(len(ALL_ELEMENTS))]
         B = int(rng.choice([8, 16, 32]))
         s = int(rng.choice([8, 8, 8, 7, 6, 5, 4]))
-        tp = int(rng.integers(1, 10))
-        T = int(rng.integers(1, 40))
-        H = B * int(rng.integers(1, 70))
+        tp = int(rng.integers(1, tp_max + 1))
+        T = int(rng.integers(1, t_max + 1))
+        H = B * int(rng.integers(1, h_blocks + 1))
         cases.append((k, x, y, B, s, tp, T, H))
     return cases
 
 
-@pytest.mark.parametrize("k,x,y,B,s,tp,T,H", random_cases(96, 20241109))
-def test_random_configurations(mxc, oracle_mod, k, x, y, B, s, tp, T, H):
+def check_random_configuration(mxc, oracle_mod, k, x, y, B, s, tp, T, H):
     """Formats, scale widths, tp, shapes (ragged, not multiples of 32 elements included) and
     stress inputs drawn from a seeded generator; every entry point against the oracle."""
     fo, fg = oracle_mod.Format(x, y, B, s), mxc.Format(x, y, B, s)
@@ -896,3 +895,15 @@ def test_random_configurations(mxc, oracle_mod, k, x, y, B, s, tp, T, H):
     for got in ([rq] if fused is None else [rq, fused]):
         assert np.array_equal(host_scales(oracle_mod, fo, got[1], os2.shape), os2)
         assert np.array_equal(host(got[0]).reshape(T, -1), oracle_mod.pack(fo, oc2))
+
+
+@pytest.mark.parametrize("k,x,y,B,s,tp,T,H", random_cases(96, 20241109))
+def test_random_configurations(mxc, oracle_mod, k, x, y, B, s, tp, T, H):
+    check_random_configuration(mxc, oracle_mod, k, x, y, B, s, tp, T, H)
+
+
+@pytest.mark.parametrize("k,x,y,B,s,tp,T,H", random_cases(32, 20241127, tp_max=32, t_max=150, h_blocks=160))
+def test_random_configurations_many_ranks_many_tiles(mxc, oracle_mod, k, x, y, B, s, tp, T, H):
+    """The same with up to 32 partials (more than 8 take the reduce kernel's general instance) and
+    tensors of up to a few hundred wave tiles."""
+    check_random_configuration(mxc, oracle_mod, 1000 + k, x, y, B, s, tp, T, H)
