@@ -17,7 +17,7 @@ carry no instrumentation.  `roofline` is for the kernel that takes most of the s
 algorithmic bytes per launch / average kernel duration, against the 8 TB/s HBM peak.  The
 durations come from an instrumented pass right after the timed region: the same steps again,
 every launch stamping a pair of HIP events at the kernel's own begin and end
-(mxc_time_next_launch), at least 24 launches per kernel whatever --steps is.  `cpu_baseline` is
+(mxc_time_next_launch), at least 50 launches per kernel whatever --steps is.  `cpu_baseline` is
 the CPU oracle timed on the same workload, for context.  The untimed `sweep` adds the other
 element formats of the configuration, the other forms of the reduction, and the requantize
 pipelines of the two larger configurations, each kernel timed the same way.
@@ -36,7 +36,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-MIN_TIMED_LAUNCHES = 24        # per kernel, in the instrumented pass and in the sweep
+MIN_TIMED_LAUNCHES = 50        # per kernel, in the instrumented pass and in the sweep
 QUANTIZE_KERNEL = "quantize_kernel"
 REDUCE_KERNEL = "dequant_reduce_tile_kernel"
 
@@ -204,7 +204,8 @@ class KernelTimer:
 def rate(nbytes, samples_ms):
     ms = float(np.mean(samples_ms))
     gbs = nbytes / ms / 1e6
-    return {"ms": ms, "hbm_GBps": gbs, "frac": gbs / HBM_PEAK_GBS, "launches_timed": len(samples_ms)}
+    return {"ms": ms, "median_ms": float(np.median(samples_ms)), "min_ms": float(np.min(samples_ms)),
+            "hbm_GBps": gbs, "frac": gbs / HBM_PEAK_GBS, "launches_timed": len(samples_ms)}
 
 
 def device_partials(w, torch):

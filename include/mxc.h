@@ -89,7 +89,7 @@ typedef enum { MXC_F32 = 0, MXC_BF16 = 1 } mxc_dtype;
 /* Human-readable text for a status code; never NULL. */
 const char *mxc_strerror(int status);
 
-/* Library version string, e.g. "mxc 0.1 gfx950". */
+/* Library version string, e.g. "mxc 0.2 gfx950". */
 const char *mxc_version(void);
 
 /* Sizes of the packed arrays for one [tokens x hidden] tensor (host only, closed form):

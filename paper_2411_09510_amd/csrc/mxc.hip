@@ -132,7 +132,7 @@ const char *mxc_strerror(int status)
     }
 }
 
-const char *mxc_version(void) { return "mxc 0.1 gfx950"; }
+const char *mxc_version(void) { return "mxc 0.2 gfx950"; }
 
 int mxc_packed_sizes(const mxc_format *fmt, int64_t tokens, int64_t hidden, size_t *code_bytes,
                      size_t *scale_bytes)
