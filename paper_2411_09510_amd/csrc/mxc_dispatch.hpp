@@ -23,19 +23,20 @@ constexpr bool kQuantNTL = true, kQuantNTS = true;
 // nontemporal stores: measured 5 % faster than plain ones whenever the outputs of successive
 // calls do not all fit the 256 MB last-level cache
 constexpr bool kReduceNTL = true, kReduceNTS = true;
-// Tile-form reduce: ranks whose loads are issued together (rc) and how 3-, 5- and 6-bit codes are
-// fetched (stage: 0 = each lane loads its own dwords, 1 = contiguous 128-bit loads redistributed
-// through LDS, 2 = the same with loads that write LDS directly), per code width and kernel form,
-// each the fastest measured at the Llama-70B-shaped configuration (tp 8, 4096 x 8192).
+// Reduce kernel: ranks whose loads are issued together (rc) and whether the codes of a full tile
+// are fetched through LDS (contiguous 128-bit loads that write LDS directly) or by each lane
+// loading its own dwords, per code width and kernel form, each the fastest measured at the
+// Llama-70B-shaped configuration (tp 8, 4096 x 8192).
 struct TileShape {
-    int rc, stage;
+    int rc;
+    bool via_lds;
 };
 constexpr TileShape tile_shape(int code_bits, bool out_bf16, bool fused, bool own)
 {
-    if (code_bits == 4) return own ? TileShape{8, 2} : TileShape{8, 0};
-    if (code_bits == 5) return own ? TileShape{8, 0} : (out_bf16 || fused) ? TileShape{8, 2} : TileShape{2, 2};
-    if (code_bits == 6) return (fused || own) ? TileShape{4, 2} : TileShape{8, 2};
-    return {4, 2};
+    if (code_bits == 4) return own ? TileShape{8, true} : TileShape{8, false};
+    if (code_bits == 5) return own ? TileShape{8, false} : (out_bf16 || fused) ? TileShape{8, true} : TileShape{2, true};
+    if (code_bits == 6) return (fused || own) ? TileShape{4, true} : TileShape{8, true};
+    return {4, true};
 }
 // the copy probe: one 16-byte piece per lane, nontemporal (measured: 0.81 of peak against 0.77 with
 // plain loads and stores, and against 0.67-0.77 for every form that moves more per wave)
@@ -137,7 +138,7 @@ int reduce_any(const mxc_format *f, const ReduceArgs &a, hipStream_t st)
         const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads));
         constexpr TileShape ts = tile_shape(E::bits, OUT_BF16, false, OWN);
         return launch(dequant_reduce_tile_kernel<E, B, OUT_BF16, ts.rc, kReduceNTL, kReduceNTS, kHw,
-                                                 false, OWN, kThreads, ts.stage>,
+                                                 false, OWN, kThreads, ts.via_lds>,
                       grid, st, a);
     });
 }

@@ -675,7 +675,7 @@ struct ChunkBits {
 // Loads the lane's share of one rank's arrays for the wave tile that starts at chunk
 // `wave_chunk0`.  A lane that is not `on` (past the end, a rank beyond tp, the own rank of the OWN
 // form) loads nothing and reads as code 0 with "e = 0".  STAGED: the codes of a full wave tile
-// (`full`) are left to load_codes_staged and only the scales are loaded here.  `tail_units` is 0
+// (`full`) are left to request_codes_to_lds and only the scales are loaded here.  `tail_units` is 0
 // for a whole chunk; the tensor's last chunk holds only 1 to 3 units of 8 elements when the size
 // is not a multiple of 32 (blocks of 8 or 16), and that one lane fetches its bytes one by one so
 // that nothing past the arrays is read.  `units` is the tensor's size in units.
@@ -1078,63 +1078,13 @@ __device__ __forceinline__ void requantize_sums(const float (&acc)[32], void *co
     }
 }
 
-// Loads the code dwords of RC ranks for a full wave tile (64 valid chunks) with contiguous
-// 128-bit loads: a rank's 64 chunks are 16*W pieces of 16 bytes, piece p going to lane p % 64, so
-// every load instruction covers whole cache lines (a lane's own W dwords are 4*W bytes apart,
-// and loading them directly touches each line with several instructions).  The pieces pass
-// through the wave's LDS area `t` (RC * 16 * W pieces), from which each lane reads its W dwords.
-// Rank r0 + i is loaded when `on[i]`; the others read as zero.  Not for W == 4, where a chunk is
-// one piece already.
-template <int W, int RC, bool NTL>
-__device__ __forceinline__ void load_codes_staged(uint32_t (&cw)[RC][W], u32x4 *t, const void *(&codes)[RC],
-                                                  const bool (&on)[RC], size_t wave_chunk0, int lane)
-{
-    constexpr int NP = 16 * W;                   // pieces per rank: 48, 80 or 96
-    constexpr int K = (NP + 63) / 64;            // load instructions per rank
-    u32x4 pv[RC][K];
-#pragma unroll
-    for (int i = 0; i < RC; ++i) {
-        const u32x4 *src = (const u32x4 *)((const uint32_t *)codes[i] + wave_chunk0 * W);
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-            const int p = k * 64 + lane;
-            pv[i][k] = (on[i] && p < NP) ? ld<NTL>(src + p) : u32x4{0u, 0u, 0u, 0u};
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < RC; ++i)
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-            const int p = k * 64 + lane;
-            if (p < NP) t[i * NP + p] = pv[i][k];
-        }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    const uint32_t *tw = (const uint32_t *)t;
-#pragma unroll
-    for (int i = 0; i < RC; ++i) {
-        if (W % 2 == 0) {
-            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-#pragma unroll
-            for (int k = 0; k < W / 2; ++k) {
-                const u32x2 v = *(const u32x2 *)(tw + i * NP * 4 + lane * W + 2 * k);
-                cw[i][(2 * k) < W ? 2 * k : 0] = v.x;
-                cw[i][(2 * k + 1) < W ? 2 * k + 1 : 0] = v.y;
-            }
-        } else {
-#pragma unroll
-            for (int k = 0; k < W; ++k) cw[i][k] = tw[i * NP * 4 + lane * W + k];
-        }
-    }
-    // the area is free again once every lane has read its dwords
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-}
-
-// The same redistribution with loads that write LDS directly (no registers in between): the
-// pieces of RC ranks are requested here; once the wave has waited for its vector-memory counter
-// to reach zero, read_codes_from_lds hands each lane its W dwords.
+// Fetches the code dwords of RC ranks for a full wave tile (64 valid chunks) through LDS: a rank's
+// 64 chunks are 16*W pieces of 16 bytes, piece p requested by lane p % 64 with a load that writes
+// LDS directly (no registers in between), so every load instruction covers whole cache lines (a
+// lane's own W dwords are 4*W bytes apart, and loading them directly touches each line with
+// several instructions).  The pieces of RC ranks are requested here into the wave's LDS area
+// `t` (RC * 16 * W pieces); once the wave has waited for its vector-memory counter to reach
+// zero, read_codes_from_lds hands each lane its W dwords.  Rank i is fetched when `on[i]`.
 template <int W, int RC, bool NTL>
 __device__ __forceinline__ void request_codes_to_lds(u32x4 *t, const void *(&codes)[RC], const bool (&on)[RC],
                                                      size_t wave_chunk0, int lane)
@@ -1187,15 +1137,14 @@ __device__ __forceinline__ void read_codes_from_lds(uint32_t (&cw)[W], const u32
 // more ranks — with each lane loading its own dwords under bounds checks, two ranks at a time.
 constexpr int kFastRanks = 8;
 
-template <class E, int B, bool OUT_BF16, int RC, bool NTL, bool NTS, bool HW, bool FUSED, bool OWN, int STAGE,
+template <class E, int B, bool OUT_BF16, int RC, bool NTL, bool NTS, bool HW, bool FUSED, bool OWN, bool VIA_LDS,
           bool FAST, bool S8>
 __device__ __forceinline__ void reduce_wave_tile(const ReduceArgs &a, u32x4 *t, int raw_offset, size_t wave_chunk0,
                                                  int lane)
 {
     constexpr int NB = 32 / B;                   // blocks (scales) per chunk
     constexpr int W = E::bits;                   // dwords of codes per chunk
-    constexpr bool kStaged = FAST && (STAGE == 2 || (STAGE == 1 && W != 4));
-    constexpr bool kDma = kStaged && STAGE == 2;
+    constexpr bool kDma = FAST && VIA_LDS;       // codes through LDS (full tiles only)
     constexpr bool kCoopScales = FAST && !S8;    // narrow scales of a full tile: one load per rank
     const size_t nchunks = (a.units + 3) / 4;    // the last one may hold only 1 to 3 units
     const bool valid = FAST || wave_chunk0 + (size_t)lane < nchunks;
@@ -1249,17 +1198,9 @@ __device__ __forceinline__ void reduce_wave_tile(const ReduceArgs &a, u32x4 *t, 
             on[i] = r < a.tp && !(OWN && r == a.own_rank);
             cptr[i] = FAST ? cp_all[FAST ? rr : 0] : a.codes[rr];
             const void *sptr = FAST ? sp_all[FAST ? rr : 0] : a.scales[rr];
-            // with staged code loads this fetches the scales only
-            load_chunk<E, B, NTL, kStaged, kCoopScales>(g[i], cptr[i], sptr, wave_chunk0, lane, valid && on[i], sf,
+            // with codes fetched through LDS this loads the scales only
+            load_chunk<E, B, NTL, kDma, kCoopScales>(g[i], cptr[i], sptr, wave_chunk0, lane, valid && on[i], sf,
                                                         a.units, FAST, tail_units);
-        }
-        if (kStaged && !kDma) {
-            uint32_t cw[RC][W];
-            load_codes_staged<W, RC, NTL>(cw, t, cptr, on, wave_chunk0, lane);
-#pragma unroll
-            for (int i = 0; i < RC; ++i)
-#pragma unroll
-                for (int k = 0; k < W; ++k) g[i].cw[k] = cw[i][k];
         }
         if (kDma) {
             request_codes_to_lds<W, RC, NTL>(t, cptr, on, wave_chunk0, lane);
@@ -1315,12 +1256,11 @@ __device__ __forceinline__ void reduce_wave_tile(const ReduceArgs &a, u32x4 *t, 
 // RC: ranks whose loads are issued together (a divisor of kFastRanks).  FUSED: instead of storing
 // the sums, quantize them again in the lane that holds them and store codes and scales;
 // bit-identical to running the unfused kernels one after the other.  OWN: rank a.own_rank
-// contributes its uncompressed bf16 partial.  STAGE: how the codes of a full tile are fetched: 0 =
-// each lane loads its own dwords; 1 = contiguous 16-byte pieces redistributed through LDS
-// (load_codes_staged; 3-, 5- and 6-bit codes); 2 = the same with loads that write LDS directly
-// (request_codes_to_lds; any width).  WG: threads per workgroup (a multiple of 64).
+// contributes its uncompressed bf16 partial.  VIA_LDS: the codes of a full tile are fetched
+// through LDS (request_codes_to_lds) instead of by each lane loading its own dwords.  WG: threads
+// per workgroup (a multiple of 64).
 template <class E, int B, bool OUT_BF16, int RC, bool NTL, bool NTS, bool HW, bool FUSED = false,
-          bool OWN = false, int WG = kThreads, int STAGE = 0>
+          bool OWN = false, int WG = kThreads, bool VIA_LDS = false>
 __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
 {
     static_assert(!(FUSED && OWN), "the fused form has no own-raw variant");
@@ -1330,7 +1270,7 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
     // LDS per wave, in 16-byte pieces: the output exchange, the staging of code pieces and the
     // own rank's raw pieces use the same area one after the other
     constexpr int kOutPieces = FUSED ? 0 : 64 * OC;
-    constexpr int kStagePieces = (STAGE == 2 || (STAGE == 1 && W != 4)) ? RC * 16 * W : 0;
+    constexpr int kStagePieces = VIA_LDS ? RC * 16 * W : 0;
     constexpr int kMainPieces = kOutPieces > kStagePieces ? kOutPieces : kStagePieces;
     // OWN: the raw pieces get 256 more behind it (the general instance, which passes them
     // through the main area, needs at least as many there)
@@ -1348,11 +1288,11 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
     u32x4 *t = tile[kPieces > 0 ? wave : 0];
     const bool fast = wave_chunk0 + 64 <= a.units / 4 && a.tp <= kFastRanks;
     if (fast && a.sf.sbits == 8)
-        reduce_wave_tile<E, B, OUT_BF16, RC, NTL, NTS, HW, FUSED, OWN, STAGE, true, true>(a, t, kRawOffset, wave_chunk0, lane);
+        reduce_wave_tile<E, B, OUT_BF16, RC, NTL, NTS, HW, FUSED, OWN, VIA_LDS, true, true>(a, t, kRawOffset, wave_chunk0, lane);
     else if (fast)
-        reduce_wave_tile<E, B, OUT_BF16, RC, NTL, NTS, HW, FUSED, OWN, STAGE, true, false>(a, t, kRawOffset, wave_chunk0, lane);
+        reduce_wave_tile<E, B, OUT_BF16, RC, NTL, NTS, HW, FUSED, OWN, VIA_LDS, true, false>(a, t, kRawOffset, wave_chunk0, lane);
     else
-        reduce_wave_tile<E, B, OUT_BF16, (RC > 2 ? 2 : RC), NTL, NTS, HW, FUSED, OWN, 0, false, false>(a, t, kRawOffset, wave_chunk0,
+        reduce_wave_tile<E, B, OUT_BF16, (RC > 2 ? 2 : RC), NTL, NTS, HW, FUSED, OWN, false, false, false>(a, t, kRawOffset, wave_chunk0,
                                                                                                lane);
 }
 

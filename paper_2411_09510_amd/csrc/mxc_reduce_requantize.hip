@@ -13,7 +13,7 @@ int reduce_requantize(const mxc_format *f, const ReduceArgs &a, hipStream_t st)
         const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads));
         constexpr TileShape ts = tile_shape(E::bits, false, true, false);
         return launch(dequant_reduce_tile_kernel<E, B, false, ts.rc, kReduceNTL, kQuantNTS, kHw, true, false,
-                                                 kThreads, ts.stage>,
+                                                 kThreads, ts.via_lds>,
                       grid, st, a);
     });
 }
