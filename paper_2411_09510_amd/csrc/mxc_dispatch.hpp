@@ -63,17 +63,24 @@ inline void disarm()
 // adds no packet to the stream.  The status is the launch call's own return value: the thread's
 // sticky error state, which other users of the runtime share, is neither read nor cleared.
 template <class... Args>
-int launch(void (*kernel)(Args...), dim3 grid, hipStream_t st, Args... args)
+int launch_wg(void (*kernel)(Args...), dim3 grid, dim3 block, hipStream_t st, Args... args)
 {
     void *argv[] = {(void *)&args...};
     hipError_t err;
     if (t_start || t_stop) {
-        err = hipExtLaunchKernel((const void *)kernel, grid, dim3(kThreads), argv, 0, st, t_start, t_stop, 0);
+        err = hipExtLaunchKernel((const void *)kernel, grid, block, argv, 0, st, t_start, t_stop, 0);
         disarm();
     } else {
-        err = hipLaunchKernel((const void *)kernel, grid, dim3(kThreads), argv, 0, st);
+        err = hipLaunchKernel((const void *)kernel, grid, block, argv, 0, st);
     }
     return err == hipSuccess ? MXC_OK : MXC_ERR_HIP;
+}
+
+// Workgroups of kThreads threads.
+template <class... Args>
+int launch(void (*kernel)(Args...), dim3 grid, hipStream_t st, Args... args)
+{
+    return launch_wg(kernel, grid, dim3(kThreads), st, args...);
 }
 
 // Calls fn(Elem<x, y>{}, std::integral_constant<int, block>{}) for the format's element type and
@@ -133,6 +140,16 @@ int reduce_any(const mxc_format *f, const ReduceArgs &a, hipStream_t st)
     return for_format(f, [&](auto elem, auto block) {
         using E = decltype(elem);
         constexpr int B = decltype(block)::value;
+        // half-chunk form: E2M1 codes, at most kFastRanks ranks and a tensor of whole wave tiles
+        // (1024 elements = 128 units)
+        if constexpr (kHalfFormOk<E>) {
+            if (a.tp <= kFastRanks && a.units % 128 == 0) {
+                const size_t waves = a.units / 128;
+                constexpr int per_wg = kHalfThreads / 64;
+                return launch_wg(dequant_reduce_half_kernel<E, B, OUT_BF16, OWN, kReduceNTL, kReduceNTS>,
+                                 dim3((unsigned)((waves + per_wg - 1) / per_wg)), dim3(kHalfThreads), st, a);
+            }
+        }
         // one lane per 32-element chunk (the last chunk may be shorter), output staged through LDS
         const size_t chunks = (a.units + 3) / 4;
         const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads));

@@ -36,6 +36,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x32 __attribute__((ext_vector_type(32)));
 typedef uint32_t u32x6 __attribute__((ext_vector_type(6)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 enum HwKind { HW_NONE = 0, HW_FP4 = 1, HW_BF8 = 2, HW_FP8 = 3 };
 
@@ -753,13 +754,13 @@ __device__ __forceinline__ void load_chunk(ChunkBits<E::bits> &c, const void *co
     c.sw = sb;
 }
 
-// Second half of the cooperative scale load: `raw` is the dword this lane fetched of the tile's
-// scale-field run (lane k holds dword k).  Returns the lane's own NB fields, one per byte.  Every
-// lane of the wave must call this.
+// Second half of the cooperative scale load: `raw` is the dword this lane fetched of the wave's
+// scale-field run (lane k holds dword k).  Returns NB consecutive fields starting at field
+// `first` of the run, one per byte.  Every lane of the wave must call this.
 template <int NB>
-__device__ __forceinline__ uint32_t spread_scale_fields(uint32_t raw, int lane, int sbits)
+__device__ __forceinline__ uint32_t spread_scale_fields_at(uint32_t raw, int first, int sbits)
 {
-    const int pos = lane * NB * sbits;           // first bit of this lane's fields
+    const int pos = first * sbits;               // first bit of the wanted fields
     const int d0 = pos >> 5;
     const uint32_t lo = (uint32_t)__builtin_amdgcn_ds_bpermute(4 * d0, (int)raw);
     const uint32_t hi = (uint32_t)__builtin_amdgcn_ds_bpermute(4 * min(d0 + 1, 63), (int)raw);
@@ -768,6 +769,13 @@ __device__ __forceinline__ uint32_t spread_scale_fields(uint32_t raw, int lane, 
 #pragma unroll
     for (int n = 0; n < NB; ++n) sb |= ((bits >> (n * sbits)) & ((1u << sbits) - 1u)) << (8 * n);
     return sb;
+}
+
+// The tile form's case: the lane's own NB fields.
+template <int NB>
+__device__ __forceinline__ uint32_t spread_scale_fields(uint32_t raw, int lane, int sbits)
+{
+    return spread_scale_fields_at<NB>(raw, lane * NB, sbits);
 }
 
 // 32 five-bit codes (5 dwords of the bit stream) -> 32 six-bit slots (6 dwords), slot = code << 1.
@@ -1294,6 +1302,171 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
     else
         reduce_wave_tile<E, B, OUT_BF16, (RC > 2 ? 2 : RC), NTL, NTS, HW, FUSED, OWN, false, false, false>(a, t, kRawOffset, wave_chunk0,
                                                                                                lane);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Half-chunk form of the reduce kernel for E2M1 codes (any block size) with one scale byte per
+// block, at most kFastRanks ranks and a tensor of whole wave tiles.  A lane owns 16 consecutive
+// elements (half a chunk), a wave 1024, a workgroup of 512 threads 8192: the same bytes per
+// workgroup as the tile form, in waves half as large and twice as many, which the memory system
+// serves 3-4 % faster (with the arithmetic taken out: 45.6 against 47.2 us at 8 ranks of
+// 4096 x 8192; 8 elements per lane is slower again).  The lane's codes are 8 contiguous bytes per
+// rank, one 64-bit load; every scale byte is an exponent field the conversion accepts, so there
+// is one decode path; the 16 sums leave through the wave's LDS area as contiguous 128-bit
+// stores.  For the 6-bit hardware formats the same shape decodes 16 codes with the 32-code
+// conversion and gains nothing (E3M2: -1 % for float32 output, +3 % for bf16), so they stay on
+// the tile form.
+constexpr int kHalfThreads = 512;
+
+template <class E>
+constexpr bool kHalfFormOk = E::hw == HW_FP4;
+
+// TP: the number of ranks, a compile-time constant so that the rank pointers come in one wide
+// scalar load and all loads are issued before the first wait.
+template <class E, int B, bool OUT_BF16, bool OWN, bool NTL, bool NTS, int TP, bool S8>
+__device__ __forceinline__ void reduce_wave_half(const ReduceArgs &a, u32x4 *t, u32x4 *traw, size_t half0, int lane)
+{
+    static_assert(kHalfFormOk<E>, "format not covered by the half-chunk form");
+    constexpr int NBH = B >= 16 ? 1 : 16 / B;    // blocks whose scale the lane holds (1 or 2)
+    constexpr int ND = 2 / NBH;                  // dwords (8 codes each) under one scale
+    constexpr int OC = OUT_BF16 ? 2 : 4;         // 16-byte output pieces per lane
+    const int sbits = S8 ? 8 : a.sf.sbits;
+    const int sbias = S8 ? 127 : a.sf.sbias;
+
+    // OWN: the wave's 2 KiB of the own rank's raw values are written straight into their LDS area
+    // as 128 contiguous pieces; lane l finds its two at traw[2 l], traw[2 l + 1]
+    if constexpr (OWN) {
+        typedef const void __attribute__((address_space(1))) *gptr;
+        typedef void __attribute__((address_space(3))) *lptr;
+        const u32x4 *src = (const u32x4 *)a.own_x + half0 * 2;
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+            __builtin_amdgcn_global_load_lds((gptr)(src + k * 64 + lane), (lptr)(traw + k * 64), 16, 0, NTL ? 2 : 0);
+    }
+
+    u32x2 cw[TP];
+    uint32_t sw[TP];
+#pragma unroll
+    for (int r = 0; r < TP; ++r) {
+        if (OWN && r == a.own_rank) continue;    // that rank's codes are not read
+        cw[r] = ld<NTL>((const u32x2 *)a.codes[r] + half0 + (size_t)lane);
+        const uint8_t *sp = (const uint8_t *)a.scales[r];
+        if (!S8) {
+            // narrow scales: the wave's 1024 / B fields are a dword-aligned run of the bit
+            // stream, fetched one dword per lane and spread below
+            const int ndw = (1024 / B) * sbits / 32;
+            const uint32_t *run = (const uint32_t *)(sp + ((half0 * 16 / B * (size_t)sbits) >> 3));
+            sw[r] = lane < ndw ? ld<NTL>(run + lane) : 0u;
+        } else if (B == 32) {                     // the block's byte, shared with the other half
+            sw[r] = ld<NTL>(sp + half0 / 2 + (size_t)(lane >> 1));
+        } else if (B == 16) {
+            sw[r] = ld<NTL>(sp + half0 + (size_t)lane);
+        } else {
+            sw[r] = ld<NTL>((const uint16_t *)sp + half0 + (size_t)lane);
+        }
+    }
+
+    float acc[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[j] = kFoldStart;
+    bool poisoned[NBH];
+#pragma unroll
+    for (int n = 0; n < NBH; ++n) poisoned[n] = false;
+
+    if constexpr (OWN) {
+        __builtin_amdgcn_s_waitcnt(0);           // every counter at zero: the raw pieces are in LDS
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+#pragma unroll
+    for (int r = 0; r < TP; ++r) {
+        if (OWN && r == a.own_rank) {
+            add_raw_bf16(traw[lane * 2], acc);
+            add_raw_bf16(traw[lane * 2 + 1], acc + 8);
+            continue;
+        }
+        // the lane's first block within the wave: lanes 2k and 2k + 1 share a block of 32
+        if (!S8) sw[r] = spread_scale_fields_at<NBH>(sw[r], B == 32 ? lane >> 1 : lane * NBH, sbits);
+#pragma unroll
+        for (int n = 0; n < NBH; ++n) {
+            // a scale byte is the exponent field the conversion takes (code 255 marks a
+            // non-finite block: its sums are replaced below); a narrow code is re-biased to one
+            const uint32_t sc = (sw[r] >> (8 * n)) & 0xFFu;
+            poisoned[n] = poisoned[n] || (S8 && sc == 255u);
+            const float hs = __uint_as_float((S8 ? min(sc, 254u) : sc + (uint32_t)(127 - sbias)) << 23);
+#pragma unroll
+            for (int h = 0; h < ND; ++h) {
+                const uint32_t v = cw[r][n * ND + h];
+                float *d = acc + 8 * (n * ND + h);
+                const f32x2 r0 = cvt_fp4_pair<0>(v, hs), r1 = cvt_fp4_pair<1>(v, hs);
+                const f32x2 r2 = cvt_fp4_pair<2>(v, hs), r3 = cvt_fp4_pair<3>(v, hs);
+                d[0] += r0.x; d[1] += r0.y; d[2] += r1.x; d[3] += r1.y;
+                d[4] += r2.x; d[5] += r2.y; d[6] += r3.x; d[7] += r3.y;
+            }
+        }
+    }
+#pragma unroll
+    for (int n = 0; n < NBH; ++n)
+        if (poisoned[n]) {
+#pragma unroll
+            for (int j = 0; j < 16 / NBH; ++j) acc[n * (16 / NBH) + j] = __uint_as_float(0x7FC00000u);
+        }
+
+    // exchange through LDS as in store_sums: piece c of lane l sits at slot (c + l) % OC of row l
+#pragma unroll
+    for (int c = 0; c < OC; ++c) {
+        u32x4 v;
+        if (OUT_BF16) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                v[j] = f32_to_bf16_rne(acc[8 * c + 2 * j]) | (f32_to_bf16_rne(acc[8 * c + 2 * j + 1]) << 16);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = __float_as_uint(acc[4 * c + j]);
+        }
+        t[lane * OC + ((c + lane) & (OC - 1))] = v;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    u32x4 *out = (u32x4 *)a.out + half0 * OC;
+#pragma unroll
+    for (int k = 0; k < OC; ++k) {
+        const int g = k * 64 + lane;             // piece index within the wave's output
+        const int l = g / OC, c = g % OC;
+        st<NTS>(out + g, t[l * OC + ((c + l) & (OC - 1))]);
+    }
+}
+
+template <class E, int B, bool OUT_BF16, bool OWN, bool NTL, bool NTS>
+__global__ __launch_bounds__(kHalfThreads) void dequant_reduce_half_kernel(ReduceArgs a)
+{
+    constexpr int OC = OUT_BF16 ? 2 : 4;
+    // per wave: the output exchange area, and behind it the own rank's raw pieces
+    __shared__ u32x4 tile[kHalfThreads / 64][64 * OC + (OWN ? 128 : 0)];
+    const int lane = (int)(threadIdx.x & 63);
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    // first half-chunk of the wave; a half-chunk is two units
+    const size_t half0 = ((size_t)blockIdx.x * (kHalfThreads / 64) + (size_t)wave) * 64;
+    if (half0 * 2 >= a.units) return;            // the whole wave
+    u32x4 *t = tile[wave];
+    // the rank count and the scale width become compile-time constants of the body
+    auto with_tp = [&](auto s8) {
+        constexpr bool S8 = decltype(s8)::value;
+        switch (a.tp) {
+        case 1: reduce_wave_half<E, B, OUT_BF16, OWN, NTL, NTS, 1, S8>(a, t, t + 64 * OC, half0, lane); break;
+        case 2: reduce_wave_half<E, B, OUT_BF16, OWN, NTL, NTS, 2, S8>(a, t, t + 64 * OC, half0, lane); break;
+        case 3: reduce_wave_half<E, B, OUT_BF16, OWN, NTL, NTS, 3, S8>(a, t, t + 64 * OC, half0, lane); break;
+        case 4: reduce_wave_half<E, B, OUT_BF16, OWN, NTL, NTS, 4, S8>(a, t, t + 64 * OC, half0, lane); break;
+        case 5: reduce_wave_half<E, B, OUT_BF16, OWN, NTL, NTS, 5, S8>(a, t, t + 64 * OC, half0, lane); break;
+        case 6: reduce_wave_half<E, B, OUT_BF16, OWN, NTL, NTS, 6, S8>(a, t, t + 64 * OC, half0, lane); break;
+        case 7: reduce_wave_half<E, B, OUT_BF16, OWN, NTL, NTS, 7, S8>(a, t, t + 64 * OC, half0, lane); break;
+        default: reduce_wave_half<E, B, OUT_BF16, OWN, NTL, NTS, 8, S8>(a, t, t + 64 * OC, half0, lane); break;
+        }
+    };
+    if (a.sf.sbits == 8) with_tp(std::true_type{});
+    else with_tp(std::false_type{});
 }
 
 // ---------------------------------------------------------------------------------------------

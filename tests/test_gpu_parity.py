@@ -390,6 +390,50 @@ def test_reduce_narrow_scale_formats(mxc, oracle_mod, s):
         assert same_f32(host(own), oracle_mod.dequant_reduce_own(fo, 2, own_bits, cs, ss))
 
 
+@pytest.mark.parametrize("B", [8, 16, 32])
+@pytest.mark.parametrize("s", [8, 7, 5, 4])
+def test_reduce_e2m1_tensors_of_whole_kilo_element_tiles(mxc, oracle_mod, B, s):
+    """E2M1 tensors whose size is a multiple of 1024 elements take a form of the reduce kernel of
+    their own (16 elements per lane, 1024 per wave, the rank count a compile-time constant): every
+    rank count it covers and the first beyond (which goes back to the general form), 19 wave
+    tiles (two workgroups and part of a third), arbitrary codes, the special scale codes, float32
+    and bf16 output, and the own-raw form at every own rank."""
+    rng = np.random.default_rng(1000 + 10 * B + s)
+    T, H = 19, 1024
+    fo, fg = oracle_mod.Format(2, 1, B, s), mxc.Format(2, 1, B, s)
+    smax = 255 if s == 8 else 2 ** s - 1
+    for tp in range(1, 10):
+        cs = [rng.integers(0, 16, size=(T, H), dtype=np.uint8) for _ in range(tp)]
+        ss = []
+        for r in range(tp):
+            lo = 100 if s == 8 else 0
+            v = rng.integers(lo, min(lo + 60, smax + 1), size=(T, H // B), dtype=np.uint8)
+            v[0] = rng.integers(0, smax + 1, size=H // B)
+            v[1, r::3] = 0
+            v[2, r::5] = smax - 1 if s == 8 else smax
+            v[3, r::7] = smax
+            ss.append(v)
+        cs[0][4] = 8                                   # a row of -0 in every rank stays -0
+        for r in range(1, tp):
+            cs[r][4] = 8
+        out = check_reduce(mxc, oracle_mod, fo, fg, cs, ss, T, H)
+        assert np.all(np.signbit(host(out)[4]))
+        if tp > 8:
+            continue
+        packed = [torch.from_numpy(oracle_mod.pack(fo, c)).cuda() for c in cs]
+        scales = [dev_scales(oracle_mod, fo, v) for v in ss]
+        own_bits = workloads.f32_to_bf16_bits(rng.standard_normal((T, H)).astype(np.float32) * 3.0)
+        for own in range(tp):
+            got = mxc.dequant_reduce_own(fg, own, dev_bf16(own_bits), packed, scales)
+            got16 = mxc.dequant_reduce_own(fg, own, dev_bf16(own_bits), packed, scales,
+                                           out_dtype=torch.bfloat16)
+            torch.cuda.synchronize()
+            want = oracle_mod.dequant_reduce_own(fo, own, own_bits, cs, ss)
+            assert same_f32(host(got), want), (tp, own)
+            assert np.array_equal(host(got16.view(torch.int16)).view(np.uint16),
+                                  oracle_mod.round_to_bf16(want)), (tp, own)
+
+
 # ------------------------------------------------------------------------ requantize --------
 
 @pytest.mark.parametrize("x,y,B", [(2, 1, 16), (2, 1, 32), (2, 2, 32), (3, 2, 32), (1, 3, 8)])
