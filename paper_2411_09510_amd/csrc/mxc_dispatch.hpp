@@ -146,7 +146,7 @@ int reduce_any(const mxc_format *f, const ReduceArgs &a, hipStream_t st)
             if (a.tp <= kFastRanks && a.units % 128 == 0) {
                 const size_t waves = a.units / 128;
                 constexpr int per_wg = kHalfThreads / 64;
-                return launch_wg(dequant_reduce_half_kernel<E, B, OUT_BF16, OWN, kReduceNTL, kReduceNTS>,
+                return launch_wg(dequant_reduce_half_kernel<E, B, OUT_BF16, OWN, false, kReduceNTL, kReduceNTS>,
                                  dim3((unsigned)((waves + per_wg - 1) / per_wg)), dim3(kHalfThreads), st, a);
             }
         }

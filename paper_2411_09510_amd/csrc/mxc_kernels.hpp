@@ -1323,7 +1323,7 @@ constexpr bool kHalfFormOk = E::hw == HW_FP4;
 
 // TP: the number of ranks, a compile-time constant so that the rank pointers come in one wide
 // scalar load and all loads are issued before the first wait.
-template <class E, int B, bool OUT_BF16, bool OWN, bool NTL, bool NTS, int TP, bool S8>
+template <class E, int B, bool OUT_BF16, bool OWN, bool FUSED, bool NTL, bool NTS, int TP, bool S8>
 __device__ __forceinline__ void reduce_wave_half(const ReduceArgs &a, u32x4 *t, u32x4 *traw, size_t half0, int lane)
 {
     static_assert(kHalfFormOk<E>, "format not covered by the half-chunk form");
@@ -1413,6 +1413,45 @@ __device__ __forceinline__ void reduce_wave_half(const ReduceArgs &a, u32x4 *t, 
             for (int j = 0; j < 16 / NBH; ++j) acc[n * (16 / NBH) + j] = __uint_as_float(0x7FC00000u);
         }
 
+    if constexpr (FUSED) {
+        // quantize the sums again, with the quantizer's rule on binary32 input: a block of 32 is
+        // shared with the neighbouring lane, smaller blocks are the lane's own
+        const ScaleFmt sf = S8 ? ScaleFmt{8, 127, 254, 255, 1} : a.sf;
+        u32x2 cq = {0u, 0u};
+        uint32_t sq = 0;                         // the lane's NBH scale codes, sbits apart
+#pragma unroll
+        for (int n = 0; n < NBH; ++n) {
+            uint32_t m = 0;
+#pragma unroll
+            for (int j = 0; j < 16 / NBH; ++j) m = max(m, __float_as_uint(acc[n * (16 / NBH) + j]) & 0x7FFFFFFFu);
+            if (B == 32) m = max(m, dpp<quad_perm(1, 0, 3, 2)>(m));
+            int sc = 0;
+#pragma unroll
+            for (int h = 0; h < ND; ++h) {
+                const float *d = acc + 8 * (n * ND + h);
+                const u32x4 w2[2] = {{__float_as_uint(d[0]), __float_as_uint(d[1]), __float_as_uint(d[2]), __float_as_uint(d[3])},
+                                     {__float_as_uint(d[4]), __float_as_uint(d[5]), __float_as_uint(d[6]), __float_as_uint(d[7])}};
+                cq[n * ND + h] = (uint32_t)encode_unit<E, true, true>(w2, (int)(m >> 23), sf, &sc);
+            }
+            sq |= (uint32_t)sc << (n * sbits);
+        }
+        st<NTS>((u32x2 *)a.codes_out + half0 + (size_t)lane, cq);
+        uint8_t *sp = (uint8_t *)a.scales_out;
+        if (!S8) {
+            // the wave's 1024 / B fields are a whole number of bytes of the stream
+            uint8_t *run = sp + ((half0 * 16 / B * (size_t)sbits) >> 3);
+            if (B == 32) store_packed_fields<2>(run, sq, sbits, 32);
+            else store_packed_fields<1>(run, sq, NBH * sbits, 64);
+        } else if (B == 32) {
+            if ((lane & 1) == 0) sp[half0 / 2 + (size_t)(lane >> 1)] = (uint8_t)sq;
+        } else if (B == 16) {
+            sp[half0 + (size_t)lane] = (uint8_t)sq;
+        } else {
+            ((uint16_t *)sp)[half0 + (size_t)lane] = (uint16_t)sq;
+        }
+        return;
+    }
+
     // exchange through LDS as in store_sums: piece c of lane l sits at slot (c + l) % OC of row l
 #pragma unroll
     for (int c = 0; c < OC; ++c) {
@@ -1439,30 +1478,32 @@ __device__ __forceinline__ void reduce_wave_half(const ReduceArgs &a, u32x4 *t, 
     }
 }
 
-template <class E, int B, bool OUT_BF16, bool OWN, bool NTL, bool NTS>
+template <class E, int B, bool OUT_BF16, bool OWN, bool FUSED, bool NTL, bool NTS>
 __global__ __launch_bounds__(kHalfThreads) void dequant_reduce_half_kernel(ReduceArgs a)
 {
-    constexpr int OC = OUT_BF16 ? 2 : 4;
+    static_assert(!(FUSED && OWN), "the fused form has no own-raw variant");
+    constexpr int OC = FUSED ? 0 : OUT_BF16 ? 2 : 4;
     // per wave: the output exchange area, and behind it the own rank's raw pieces
-    __shared__ u32x4 tile[kHalfThreads / 64][64 * OC + (OWN ? 128 : 0)];
+    constexpr int kPieces = 64 * OC + (OWN ? 128 : 0);
+    __shared__ u32x4 tile[kHalfThreads / 64][kPieces > 0 ? kPieces : 1];
     const int lane = (int)(threadIdx.x & 63);
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     // first half-chunk of the wave; a half-chunk is two units
     const size_t half0 = ((size_t)blockIdx.x * (kHalfThreads / 64) + (size_t)wave) * 64;
     if (half0 * 2 >= a.units) return;            // the whole wave
-    u32x4 *t = tile[wave];
+    u32x4 *t = tile[kPieces > 0 ? wave : 0];
     // the rank count and the scale width become compile-time constants of the body
     auto with_tp = [&](auto s8) {
         constexpr bool S8 = decltype(s8)::value;
         switch (a.tp) {
-        case 1: reduce_wave_half<E, B, OUT_BF16, OWN, NTL, NTS, 1, S8>(a, t, t + 64 * OC, half0, lane); break;
-        case 2: reduce_wave_half<E, B, OUT_BF16, OWN, NTL, NTS, 2, S8>(a, t, t + 64 * OC, half0, lane); break;
-        case 3: reduce_wave_half<E, B, OUT_BF16, OWN, NTL, NTS, 3, S8>(a, t, t + 64 * OC, half0, lane); break;
-        case 4: reduce_wave_half<E, B, OUT_BF16, OWN, NTL, NTS, 4, S8>(a, t, t + 64 * OC, half0, lane); break;
-        case 5: reduce_wave_half<E, B, OUT_BF16, OWN, NTL, NTS, 5, S8>(a, t, t + 64 * OC, half0, lane); break;
-        case 6: reduce_wave_half<E, B, OUT_BF16, OWN, NTL, NTS, 6, S8>(a, t, t + 64 * OC, half0, lane); break;
-        case 7: reduce_wave_half<E, B, OUT_BF16, OWN, NTL, NTS, 7, S8>(a, t, t + 64 * OC, half0, lane); break;
-        default: reduce_wave_half<E, B, OUT_BF16, OWN, NTL, NTS, 8, S8>(a, t, t + 64 * OC, half0, lane); break;
+        case 1: reduce_wave_half<E, B, OUT_BF16, OWN, FUSED, NTL, NTS, 1, S8>(a, t, t + 64 * OC, half0, lane); break;
+        case 2: reduce_wave_half<E, B, OUT_BF16, OWN, FUSED, NTL, NTS, 2, S8>(a, t, t + 64 * OC, half0, lane); break;
+        case 3: reduce_wave_half<E, B, OUT_BF16, OWN, FUSED, NTL, NTS, 3, S8>(a, t, t + 64 * OC, half0, lane); break;
+        case 4: reduce_wave_half<E, B, OUT_BF16, OWN, FUSED, NTL, NTS, 4, S8>(a, t, t + 64 * OC, half0, lane); break;
+        case 5: reduce_wave_half<E, B, OUT_BF16, OWN, FUSED, NTL, NTS, 5, S8>(a, t, t + 64 * OC, half0, lane); break;
+        case 6: reduce_wave_half<E, B, OUT_BF16, OWN, FUSED, NTL, NTS, 6, S8>(a, t, t + 64 * OC, half0, lane); break;
+        case 7: reduce_wave_half<E, B, OUT_BF16, OWN, FUSED, NTL, NTS, 7, S8>(a, t, t + 64 * OC, half0, lane); break;
+        default: reduce_wave_half<E, B, OUT_BF16, OWN, FUSED, NTL, NTS, 8, S8>(a, t, t + 64 * OC, half0, lane); break;
         }
     };
     if (a.sf.sbits == 8) with_tp(std::true_type{});

@@ -397,7 +397,7 @@ def test_reduce_e2m1_tensors_of_whole_kilo_element_tiles(mxc, oracle_mod, B, s):
     their own (16 elements per lane, 1024 per wave, the rank count a compile-time constant): every
     rank count it covers and the first beyond (which goes back to the general form), 19 wave
     tiles (two workgroups and part of a third), arbitrary codes, the special scale codes, float32
-    and bf16 output, and the own-raw form at every own rank."""
+    and bf16 output, the fused form, and the own-raw form at every own rank."""
     rng = np.random.default_rng(1000 + 10 * B + s)
     T, H = 19, 1024
     fo, fg = oracle_mod.Format(2, 1, B, s), mxc.Format(2, 1, B, s)
@@ -422,6 +422,16 @@ def test_reduce_e2m1_tensors_of_whole_kilo_element_tiles(mxc, oracle_mod, B, s):
             continue
         packed = [torch.from_numpy(oracle_mod.pack(fo, c)).cuda() for c in cs]
         scales = [dev_scales(oracle_mod, fo, v) for v in ss]
+        # the fused form, with canaries behind both outputs
+        cb, sb = mxc.packed_sizes(fg, T, H)
+        cbuf = torch.full((cb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+        sbuf = torch.full((sb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+        cf, sf_ = mxc.dequant_reduce_requantize(fg, packed, scales, T, H, cbuf[:cb].view(T, cb // T), sbuf[:sb])
+        torch.cuda.synchronize()
+        assert (cbuf[cb:] == 0xA5).all() and (sbuf[sb:] == 0xA5).all()
+        oc, os_ = oracle_mod.quantize_f32(fo, oracle_mod.dequant_reduce(fo, cs, ss))
+        assert np.array_equal(host_scales(oracle_mod, fo, sf_, os_.shape), os_), tp
+        assert np.array_equal(host(cf), oracle_mod.pack(fo, oc)), tp
         own_bits = workloads.f32_to_bf16_bits(rng.standard_normal((T, H)).astype(np.float32) * 3.0)
         for own in range(tp):
             got = mxc.dequant_reduce_own(fg, own, dev_bf16(own_bits), packed, scales)
