@@ -1305,18 +1305,21 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
 }
 
 // ---------------------------------------------------------------------------------------------
-// Half-chunk form of the reduce kernel for E2M1 codes (any block size) with one scale byte per
-// block, at most kFastRanks ranks and a tensor of whole wave tiles.  A lane owns 16 consecutive
-// elements (half a chunk), a wave 1024, a workgroup of 512 threads 8192: the same bytes per
-// workgroup as the tile form, in waves half as large and twice as many, which the memory system
-// serves 3-4 % faster (with the arithmetic taken out: 45.6 against 47.2 us at 8 ranks of
-// 4096 x 8192; 8 elements per lane is slower again).  The lane's codes are 8 contiguous bytes per
-// rank, one 64-bit load; every scale byte is an exponent field the conversion accepts, so there
-// is one decode path; the 16 sums leave through the wave's LDS area as contiguous 128-bit
-// stores.  For the 6-bit hardware formats the same shape decodes 16 codes with the 32-code
-// conversion and gains nothing (E3M2: -1 % for float32 output, +3 % for bf16), so they stay on
-// the tile form.
+// Half-chunk form of the reduce kernel for E2M1 codes (any block size, any scale width), at most
+// kFastRanks ranks and a tensor of whole wave tiles.  A lane owns 16 consecutive elements (half a
+// chunk), a wave 1024, a workgroup of 512 threads 8192: the same bytes per workgroup as the tile
+// form, in waves half as large and twice as many.  A launch of this form gets going and drains
+// faster: 9 % less time at 1024 x 8192 elements and 8 ranks, 4 % at 4096 x 8192, 1 % at
+// 6144 x 8192; beyond that the two forms move the same bytes per second (and this one loses
+// 2-4 % when the ranks' buffers are 34 or 68 MiB apart), so the host uses it up to
+// kHalfFormMaxUnits.  The lane's codes are 8 contiguous bytes per rank, one 64-bit load; every
+// scale code gives an exponent field the conversion accepts, so there is one decode path; the 16
+// sums leave through the wave's LDS area as contiguous 128-bit stores, or (fused form) are
+// quantized again by the lane, which shares a block of 32 with its neighbour.  For the 6-bit
+// hardware formats the same shape decodes 16 codes with the 32-code conversion; with the codes
+// fetched through LDS it gains 2 % (E3M2), so they stay on the tile form.
 constexpr int kHalfThreads = 512;
+constexpr size_t kHalfFormMaxUnits = (size_t)6144 * 8192 / 8;
 
 template <class E>
 constexpr bool kHalfFormOk = E::hw == HW_FP4;
