@@ -1,13 +1,14 @@
 // Device code of the mxc library for gfx950 (wave64).
 //
-// Work decomposition shared by all kernels: a tensor [tokens x hidden] is treated as a flat
-// array (blocks never straddle rows because hidden % block == 0, and rows are packed back to
-// back, so the flat view of inputs, packed codes and scales is exact).  A "unit" is 8 consecutive
-// elements: one 128-bit load of bf16, one dword of 4-bit codes, b bytes of b-bit codes.  A block of
-// B elements is B/8 neighbouring lanes of one wave (1, 2 or 4 lanes), so the block maximum is a
-// quad-local DPP reduction and never touches LDS.  Each wave owns U * 64 consecutive units; in
+// Every kernel treats a tensor [tokens x hidden] as a flat array (blocks never straddle rows
+// because hidden % block == 0, and rows are packed back to back, so the flat view of inputs,
+// packed codes and scales is exact).  A "unit" is 8 consecutive elements: one 128-bit load of
+// bf16, one dword of 4-bit codes, b bytes of b-bit codes.  In the quantize kernels a block of B
+// elements is B/8 neighbouring lanes of one wave (1, 2 or 4 lanes), so the block maximum is a
+// quad-local DPP reduction and never touches LDS; each wave owns U * 64 consecutive units and in
 // step u lane l handles unit (wave_base + u*64 + l), which keeps every load and store instruction
-// contiguous across the wave.
+// contiguous across the wave.  The reduce kernels give a lane a chunk of 32 consecutive elements
+// (tile form) or half of one (half-chunk form); see their sections.
 //
 // Element rounding and decoding use the gfx950 scaled-conversion instructions wherever the
 // element format maps onto a hardware format bit for bit (checked exhaustively against the CPU
@@ -249,29 +250,76 @@ __device__ __forceinline__ void store_codes(uint32_t *codes, size_t unit, uint64
 // Narrow scale formats (s < 8) travel as a bit stream: block k's code at bits [k*s, (k+1)*s) of
 // the tensor's scale array, LSB first, the last byte padded with zeros.
 
-// Wave-wide store of 64/G consecutive fields of `width` bits (4..28), field f held by lane f*G in
+// Wave-wide store of 64/G consecutive fields of WIDTH bits (4..28), field f held by lane f*G in
 // `value` (fields past `nvalid` must hold 0).  `dst` is the byte where field 0 starts, which is
 // always a byte boundary because 64/G fields of any width fill a whole number of bytes.  Lane j
 // assembles byte j (and j+64, ... for wide fields) from the up to three fields that overlap it.
 // Every lane of the wave must call this, and every lane runs the same number of rounds: the
 // cross-lane reads need their source lanes active.
-template <int G>
-__device__ __forceinline__ void store_packed_fields(uint8_t *dst, uint32_t value, int width, int nvalid)
+// WIDTH is a compile-time constant so that the division below folds into a multiply (with a
+// run-time width it costs some 40 instructions per call).
+template <int G, int WIDTH>
+__device__ __forceinline__ void store_packed_fields(uint8_t *dst, uint32_t value, int nvalid)
 {
+    static_assert(WIDTH >= 4 && WIDTH <= 28, "a byte spans at most three fields");
     constexpr int NF = 64 / G;
+    constexpr int kRounds = (((NF * WIDTH) >> 3) + 63) >> 6;
     const int lane = (int)(threadIdx.x & 63);
-    const int nbytes = (nvalid * width + 7) >> 3;
-    const int rounds = (((NF * width) >> 3) + 63) >> 6;
-    for (int t = 0; t < rounds; ++t) {
+    const int nbytes = (nvalid * WIDTH + 7) >> 3;
+#pragma unroll
+    for (int t = 0; t < kRounds; ++t) {
         const int j = lane + 64 * t;
-        const int f0 = (8 * j) / width, off = 8 * j - f0 * width;
+        const int f0 = (8 * j) / WIDTH, off = 8 * j - f0 * WIDTH;
         uint32_t bits = 0;
 #pragma unroll
         for (int k = 0; k < 3; ++k) {
             const int f = f0 + k;
             const uint32_t v = (uint32_t)__builtin_amdgcn_ds_bpermute(4 * min(f, NF - 1) * G, (int)value);
-            const int sh = k * width - off;                   // negative only for k == 0
+            const int sh = k * WIDTH - off;                   // negative only for k == 0
             if (f < NF && sh < 8) bits |= sh >= 0 ? v << sh : v >> -sh;
+        }
+        if (j < nbytes) dst[j] = (uint8_t)bits;
+    }
+}
+
+// Calls fn(std::integral_constant<int, s>{}) for the narrow scale width s = 4..7 (wave-uniform).
+template <class Fn>
+__device__ __forceinline__ void with_scale_width(int sbits, Fn fn)
+{
+    switch (sbits) {
+    case 4: fn(std::integral_constant<int, 4>{}); break;
+    case 5: fn(std::integral_constant<int, 5>{}); break;
+    case 6: fn(std::integral_constant<int, 6>{}); break;
+    default: fn(std::integral_constant<int, 7>{}); break;
+    }
+}
+
+// The quantize kernels' form of the same store, for all U steps of a wave at once and a scale
+// width known at compile time (the division below folds into a multiply): the wave's U * 64/G
+// fields of WIDTH bits (4..7) are consecutive in the stream; the field of step u, block k is held
+// by lane k*G in byte u of `value` (0 for fields past `nvalid`).  Every lane of the wave must call
+// this.
+template <int G, int U, int WIDTH>
+__device__ __forceinline__ void store_packed_steps(uint8_t *dst, uint32_t value, int nvalid)
+{
+    static_assert(U <= 4 && WIDTH >= 4 && WIDTH <= 7, "one byte per step in a dword; a byte spans <= 3 fields");
+    constexpr int NF = 64 / G, NT = U * NF;
+    constexpr int kRounds = (((NT * WIDTH) >> 3) + 63) >> 6;
+    const int lane = (int)(threadIdx.x & 63);
+    const int nbytes = (nvalid * WIDTH + 7) >> 3;
+#pragma unroll
+    for (int t = 0; t < kRounds; ++t) {
+        const int j = lane + 64 * t;
+        const int f0 = (8 * j) / WIDTH, off = 8 * j - f0 * WIDTH;
+        uint32_t bits = 0;
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+            const int f = f0 + k;
+            const int fc = min(f, NT - 1);
+            uint32_t v = (uint32_t)__builtin_amdgcn_ds_bpermute(4 * (fc % NF) * G, (int)value);
+            v = (v >> (8 * (fc / NF))) & 0xFFu;
+            const int sh = k * WIDTH - off;                   // negative only for k == 0
+            if (f < NT && sh < 8) bits |= sh >= 0 ? v << sh : v >> -sh;
         }
         if (j < nbytes) dst[j] = (uint8_t)bits;
     }
@@ -480,6 +528,7 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantArgs a)
     }
 
     int my_scale = 0;                            // the scale byte this lane will store
+    uint32_t narrow_scales = 0;                  // narrow scale codes of this lane's blocks, step u in byte u
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const size_t unit = wave_base + (size_t)(u * 64 + lane);
@@ -504,15 +553,8 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantArgs a)
 
         // Every lane of a block knows the block's scale.
         if (sf.sbits < 8) {
-            // packed scale stream: the 64/G scales of this wave step are a byte-aligned run
-            const size_t first_unit = wave_base + (size_t)(u * 64);
-            if (first_unit < a.units) {
-                const size_t first_block = first_unit / G;
-                const size_t left = a.units / G - first_block;
-                store_packed_fields<G>(scales + ((first_block * (size_t)sf.sbits) >> 3),
-                                       valid[u] ? (uint32_t)sc : 0u, sf.sbits,
-                                       (int)(left < (size_t)(64 / G) ? left : (size_t)(64 / G)));
-            }
+            // packed scale stream: stored for all steps at once below
+            if (valid[u]) narrow_scales |= (uint32_t)sc << (8 * u);
         } else if (U % G == 0) {
             // Over G consecutive steps lane l keeps the scale of step (l % G); after the G-th
             // step each lane stores one byte, so the wave writes 64 consecutive scale bytes.
@@ -525,6 +567,14 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantArgs a)
         } else {
             if ((lane & (G - 1)) == 0 && valid[u]) scales[unit / G] = (uint8_t)sc;
         }
+    }
+    if (sf.sbits < 8 && wave_base < a.units) {
+        // the wave's U * 64/G scale fields are a byte-aligned run of the stream
+        const size_t first_block = wave_base / G;
+        const size_t left = a.units / G - first_block;
+        const int nvalid = (int)(left < (size_t)(U * 64 / G) ? left : (size_t)(U * 64 / G));
+        uint8_t *run = scales + ((first_block * (size_t)sf.sbits) >> 3);
+        with_scale_width(sf.sbits, [&](auto w) { store_packed_steps<G, U, decltype(w)::value>(run, narrow_scales, nvalid); });
     }
 }
 
@@ -1081,8 +1131,10 @@ __device__ __forceinline__ void requantize_sums(const float (&acc)[32], void *co
 #pragma unroll
         for (int n = 0; n < NB; ++n) field |= ((sbytes >> (8 * n)) & 0xFFu) << (n * sf.sbits);
         const size_t left = nchunks - wave_chunk0;
-        store_packed_fields<1>((uint8_t *)scales_out + ((wave_chunk0 * NB * (size_t)sf.sbits) >> 3),
-                               valid ? field : 0u, NB * sf.sbits, (int)(left < 64 ? left : 64));
+        uint8_t *run = (uint8_t *)scales_out + ((wave_chunk0 * NB * (size_t)sf.sbits) >> 3);
+        with_scale_width(sf.sbits, [&](auto w) {
+            store_packed_fields<1, NB * decltype(w)::value>(run, valid ? field : 0u, (int)(left < 64 ? left : 64));
+        });
     }
 }
 
@@ -1443,8 +1495,10 @@ __device__ __forceinline__ void reduce_wave_half(const ReduceArgs &a, u32x4 *t, 
         if (!S8) {
             // the wave's 1024 / B fields are a whole number of bytes of the stream
             uint8_t *run = sp + ((half0 * 16 / B * (size_t)sbits) >> 3);
-            if (B == 32) store_packed_fields<2>(run, sq, sbits, 32);
-            else store_packed_fields<1>(run, sq, NBH * sbits, 64);
+            with_scale_width(sbits, [&](auto w) {
+                if (B == 32) store_packed_fields<2, decltype(w)::value>(run, sq, 32);
+                else store_packed_fields<1, NBH * decltype(w)::value>(run, sq, 64);
+            });
         } else if (B == 32) {
             if ((lane & 1) == 0) sp[half0 / 2 + (size_t)(lane >> 1)] = (uint8_t)sq;
         } else if (B == 16) {
