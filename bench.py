@@ -42,10 +42,10 @@ QUANTIZE_KERNEL = "quantize_kernel"
 
 def reduce_kernel(x, y, tp, tokens, hidden):
     """Name of the kernel mxc_dequant_reduce launches (as rocprofv3 prints it): E2M1 tensors of
-    whole 1024-element wave tiles, up to 6144 x 8192 elements, with at most 8 partials take the
+    whole 1024-element wave tiles, up to 6144 x 8192 elements, with 6 to 8 partials take the
     half-chunk form."""
     n = tokens * hidden
-    if (x, y) == (2, 1) and tp <= 8 and n % 1024 == 0 and n <= 6144 * 8192:
+    if (x, y) == (2, 1) and 6 <= tp <= 8 and n % 1024 == 0 and n <= 6144 * 8192:
         return "dequant_reduce_half_kernel"
     return "dequant_reduce_tile_kernel"
 

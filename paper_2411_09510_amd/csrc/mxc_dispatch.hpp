@@ -140,10 +140,10 @@ int reduce_any(const mxc_format *f, const ReduceArgs &a, hipStream_t st)
     return for_format(f, [&](auto elem, auto block) {
         using E = decltype(elem);
         constexpr int B = decltype(block)::value;
-        // half-chunk form: E2M1 codes, at most kFastRanks ranks and a tensor of whole wave tiles
-        // (1024 elements = 128 units), up to the size where it stops paying
+        // half-chunk form: E2M1 codes, 6 to 8 ranks and a tensor of whole wave tiles (1024
+        // elements = 128 units), up to the size where it stops paying
         if constexpr (kHalfFormOk<E>) {
-            if (a.tp <= kFastRanks && a.units % 128 == 0 && a.units <= kHalfFormMaxUnits) {
+            if (a.tp >= kHalfFormMinRanks && a.tp <= kFastRanks && a.units % 128 == 0 && a.units <= kHalfFormMaxUnits) {
                 const size_t waves = a.units / 128;
                 constexpr int per_wg = kHalfThreads / 64;
                 return launch_wg(dequant_reduce_half_kernel<E, B, OUT_BF16, OWN, false, kReduceNTL, kReduceNTS>,

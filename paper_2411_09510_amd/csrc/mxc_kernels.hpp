@@ -1364,7 +1364,9 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
 // faster: 9 % less time at 1024 x 8192 elements and 8 ranks, 4 % at 4096 x 8192, 1 % at
 // 6144 x 8192; beyond that the two forms move the same bytes per second (and this one loses
 // 2-4 % when the ranks' buffers are 34 or 68 MiB apart), so the host uses it up to
-// kHalfFormMaxUnits.  The lane's codes are 8 contiguous bytes per rank, one 64-bit load; every
+// kHalfFormMaxUnits.  With few ranks the launch is mostly its float32 output and the tile form's
+// larger waves do better (2 ranks: 1-15 % at every size; 4 ranks: 4-30 % below 4096 x 8192,
+// 2-3 % worse above), so it is used from kHalfFormMinRanks ranks on.  The lane's codes are 8 contiguous bytes per rank, one 64-bit load; every
 // scale code gives an exponent field the conversion accepts, so there is one decode path; the 16
 // sums leave through the wave's LDS area as contiguous 128-bit stores, or (fused form) are
 // quantized again by the lane, which shares a block of 32 with its neighbour.  For the 6-bit
@@ -1372,12 +1374,13 @@ __global__ __launch_bounds__(WG) void dequant_reduce_tile_kernel(ReduceArgs a)
 // fetched through LDS it gains 2 % (E3M2), so they stay on the tile form.
 constexpr int kHalfThreads = 512;
 constexpr size_t kHalfFormMaxUnits = (size_t)6144 * 8192 / 8;
+constexpr int kHalfFormMinRanks = 6;
 
 template <class E>
 constexpr bool kHalfFormOk = E::hw == HW_FP4;
 
-// TP: the number of ranks, a compile-time constant so that the rank pointers come in one wide
-// scalar load and all loads are issued before the first wait.
+// TP: the number of ranks (kHalfFormMinRanks..kFastRanks), a compile-time constant so that the
+// rank pointers come in one wide scalar load and all loads are issued before the first wait.
 template <class E, int B, bool OUT_BF16, bool OWN, bool FUSED, bool NTL, bool NTS, int TP, bool S8>
 __device__ __forceinline__ void reduce_wave_half(const ReduceArgs &a, u32x4 *t, u32x4 *traw, size_t half0, int lane)
 {
@@ -1548,16 +1551,12 @@ __global__ __launch_bounds__(kHalfThreads) void dequant_reduce_half_kernel(Reduc
     // first half-chunk of the wave; a half-chunk is two units
     const size_t half0 = ((size_t)blockIdx.x * (kHalfThreads / 64) + (size_t)wave) * 64;
     if (half0 * 2 >= a.units) return;            // the whole wave
+    if (a.tp < kHalfFormMinRanks || a.tp > kFastRanks) return;   // the host never launches this
     u32x4 *t = tile[kPieces > 0 ? wave : 0];
     // the rank count and the scale width become compile-time constants of the body
     auto with_tp = [&](auto s8) {
         constexpr bool S8 = decltype(s8)::value;
         switch (a.tp) {
-        case 1: reduce_wave_half<E, B, OUT_BF16, OWN, FUSED, NTL, NTS, 1, S8>(a, t, t + 64 * OC, half0, lane); break;
-        case 2: reduce_wave_half<E, B, OUT_BF16, OWN, FUSED, NTL, NTS, 2, S8>(a, t, t + 64 * OC, half0, lane); break;
-        case 3: reduce_wave_half<E, B, OUT_BF16, OWN, FUSED, NTL, NTS, 3, S8>(a, t, t + 64 * OC, half0, lane); break;
-        case 4: reduce_wave_half<E, B, OUT_BF16, OWN, FUSED, NTL, NTS, 4, S8>(a, t, t + 64 * OC, half0, lane); break;
-        case 5: reduce_wave_half<E, B, OUT_BF16, OWN, FUSED, NTL, NTS, 5, S8>(a, t, t + 64 * OC, half0, lane); break;
         case 6: reduce_wave_half<E, B, OUT_BF16, OWN, FUSED, NTL, NTS, 6, S8>(a, t, t + 64 * OC, half0, lane); break;
         case 7: reduce_wave_half<E, B, OUT_BF16, OWN, FUSED, NTL, NTS, 7, S8>(a, t, t + 64 * OC, half0, lane); break;
         default: reduce_wave_half<E, B, OUT_BF16, OWN, FUSED, NTL, NTS, 8, S8>(a, t, t + 64 * OC, half0, lane); break;

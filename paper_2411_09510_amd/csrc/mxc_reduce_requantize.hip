@@ -11,7 +11,7 @@ int reduce_requantize(const mxc_format *f, const ReduceArgs &a, hipStream_t st)
         constexpr int B = decltype(block)::value;
         // half-chunk form, as for the plain reduction
         if constexpr (kHalfFormOk<E>) {
-            if (a.tp <= kFastRanks && a.units % 128 == 0 && a.units <= kHalfFormMaxUnits) {
+            if (a.tp >= kHalfFormMinRanks && a.tp <= kFastRanks && a.units % 128 == 0 && a.units <= kHalfFormMaxUnits) {
                 const size_t waves = a.units / 128;
                 constexpr int per_wg = kHalfThreads / 64;
                 return launch_wg(dequant_reduce_half_kernel<E, B, false, false, true, kReduceNTL, kQuantNTS>,

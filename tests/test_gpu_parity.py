@@ -393,11 +393,12 @@ def test_reduce_narrow_scale_formats(mxc, oracle_mod, s):
 @pytest.mark.parametrize("B", [8, 16, 32])
 @pytest.mark.parametrize("s", [8, 7, 5, 4])
 def test_reduce_e2m1_tensors_of_whole_kilo_element_tiles(mxc, oracle_mod, B, s):
-    """E2M1 tensors whose size is a multiple of 1024 elements take a form of the reduce kernel of
-    their own (16 elements per lane, 1024 per wave, the rank count a compile-time constant): every
-    rank count it covers and the first beyond (which goes back to the general form), 19 wave
-    tiles (two workgroups and part of a third), arbitrary codes, the special scale codes, float32
-    and bf16 output, the fused form, and the own-raw form at every own rank."""
+    """E2M1 tensors whose size is a multiple of 1024 elements, reduced over 6 to 8 ranks, take a
+    form of the reduce kernel of their own (16 elements per lane, 1024 per wave, the rank count a
+    compile-time constant): every rank count from 1 to 9 (those it covers and those on either
+    side, which take the general form), 19 wave tiles (two workgroups and part of a third),
+    arbitrary codes, the special scale codes, float32 and bf16 output, the fused form, and the
+    own-raw form at every own rank."""
     rng = np.random.default_rng(1000 + 10 * B + s)
     T, H = 19, 1024
     fo, fg = oracle_mod.Format(2, 1, B, s), mxc.Format(2, 1, B, s)
