@@ -780,8 +780,8 @@ def test_quality_proxy_of_the_gpu_pipeline_equals_the_oracle_pipeline(mxc, oracl
 def test_full_size_config3_whole_tensor(mxc, oracle_mod):
     """The benchmark's launch configuration (all 8 partials of bf16 [4096 x 8192] in one batched
     launch, then one reduce), for the three element formats of the configuration: every code
-    byte and scale byte of all 8 partials and every float32 of the reduced tensor against the
-    oracle."""
+    byte and scale byte of all 8 partials and every element of the reduced tensor against the
+    oracle, in float32, in bf16, re-quantized by the fused call, and with rank 3's partial raw."""
     w = workloads.CONFIGS[3]
     parts = workloads.all_partials_bf16(w)
     xs = [dev_bf16(p) for p in parts]
@@ -799,7 +799,20 @@ def test_full_size_config3_whole_tensor(mxc, oracle_mod):
             oss.append(os_)
         want = oracle_mod.dequant_reduce(fo, ocs, oss)
         assert same_f32(host(out), want), (x, y)
-        del ocs, oss, want
+        # the other forms of the reduction the benchmark times at this size: bf16 output, the
+        # fused reduce + requantize, and the own-raw form (rank 3's view)
+        out16 = mxc.dequant_reduce(fg, codes, scales, w.tokens, w.hidden, out_dtype=torch.bfloat16)
+        cf, sf_ = mxc.dequant_reduce_requantize(fg, codes, scales, w.tokens, w.hidden)
+        own = mxc.dequant_reduce_own(fg, 3, xs[3], codes, scales)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(out16.view(torch.int16)).view(np.uint16), oracle_mod.round_to_bf16(want)), (x, y)
+        oc, os_ = oracle_mod.quantize_f32(fo, want)
+        assert np.array_equal(host(sf_), os_), (x, y)
+        assert np.array_equal(host(cf), oracle_mod.pack(fo, oc)), (x, y)
+        del oc, os_, out16, cf, sf_
+        want_own = oracle_mod.dequant_reduce_own(fo, 3, parts[3], ocs, oss)
+        assert same_f32(host(own), want_own), (x, y)
+        del ocs, oss, want, want_own, own
         cb, sb = mxc.packed_sizes(fg, w.tokens, w.hidden)
         ratio = w.tokens * w.hidden * 2 / (cb + sb)
         assert abs(ratio - 16 / (fo.bits + s / B)) < 1e-9
