@@ -20,7 +20,7 @@ every launch stamping a pair of HIP events at the kernel's own begin and end
 (mxc_time_next_launch), at least 50 launches per kernel whatever --steps is.  `cpu_baseline` is
 the CPU oracle timed on the same workload, for context.  The untimed `sweep` adds the other
 element formats of the configuration, the other forms of the reduction, and the requantize
-pipelines of the two larger configurations, each kernel timed the same way.
+pipelines of the two larger configurations and configuration 2, each kernel timed the same way.
 """
 from __future__ import annotations
 
@@ -287,6 +287,44 @@ def pipeline_block(mxc, torch, timer, w, fmt_tuple):
         "pipeline_fused_ms": q["ms"] + fz["ms"],
     }
     del xs, sets, outs, ql, dl, rq, fu
+    torch.cuda.empty_cache()
+    return block
+
+
+def small_config_block(mxc, torch, timer, w, fmt_tuple):
+    """Quantize and dequant-reduce of a configuration whose tensors fit the 256 MB last-level
+    cache several times over (configuration 2: 4 partials of bf16 [2048 x 4096]): inputs, packed
+    sets and outputs each rotate over enough copies (more than 256 MB per kind) that every launch
+    still streams from and to HBM."""
+    T, H, N = w.tokens, w.hidden, w.tp
+    f = mxc.Format(*fmt_tuple)
+    n = T * H
+    xs0 = device_partials(w, torch)
+    RX = (256 << 20) // (N * n * 2) + 2
+    RO = (256 << 20) // (n * 4) + 2
+    x_sets = [xs0] + [[t.clone() for t in xs0] for _ in range(RX - 1)]
+    cb, sb = mxc.packed_sizes(f, T, H)
+    RP = (256 << 20) // (N * (cb + sb)) + 2
+    sets = []
+    for _ in range(RP):
+        buf = torch.empty(N * (cb + sb), dtype=torch.uint8, device="cuda")
+        sets.append(([buf[r * (cb + sb): r * (cb + sb) + cb].view(T, cb // T) for r in range(N)],
+                     [buf[r * (cb + sb) + cb: (r + 1) * (cb + sb)].view(T, sb // T) for r in range(N)]))
+    outs = [torch.empty((T, H), dtype=torch.float32, device="cuda") for _ in range(RO)]
+    for k in range(RP):
+        mxc.quantize_batched(f, xs0, *sets[k])
+    ql = [mxc.prepare_quantize_batched(f, x_sets[i % RX], *sets[i % RP]) for i in range(RX * RP)]
+    dl = [mxc.prepare_dequant_reduce(f, *sets[i % RP], T, H, outs[i % RO]) for i in range(RP * RO)]
+    packed = packed_bytes(f, T, H)
+    block = {
+        "workload": w.name, "element": f"e{f.ebits}m{f.mbits}", "block": f.block, "tp": N,
+        "data": "synthetic, drawn on the device (same recipe, torch generator)",
+        "rotation": {"input_sets": RX, "packed_sets": RP, "outputs": RO},
+        "quantize": {"kernel": QUANTIZE_KERNEL, **rate(N * (n * 2 + packed), timer.each(lambda i: ql[i % len(ql)]()))},
+        "dequant_reduce_f32": {"kernel": reduce_kernel(f.ebits, f.mbits, N, T, H),
+                               **rate(N * packed + n * 4, timer.each(lambda i: dl[i % len(dl)]()))},
+    }
+    del xs0, x_sets, sets, outs, ql, dl
     torch.cuda.empty_cache()
     return block
 
@@ -593,6 +631,7 @@ def main():
     if not args.no_sweep and not args.no_pipelines and args.config == 3:
         del x_sets, sets, outs, q_launch, d_launch
         torch.cuda.empty_cache()
+        result["config2"] = small_config_block(mxc, torch, timer, workloads.CONFIGS[2], workloads.CONFIGS[2].formats[0])
         result["pipelines"] = {
             "config4_b16": pipeline_block(mxc, torch, timer, workloads.CONFIGS[4], workloads.CONFIGS[4].formats[0]),
             "config4_b32": pipeline_block(mxc, torch, timer, workloads.CONFIGS[4], workloads.CONFIGS[4].formats[1]),
