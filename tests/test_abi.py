@@ -179,3 +179,28 @@ def test_integer_types_are_one_bit_exponent_floats(oracle_mod):
         assert mxc.effective_bits(f) == k + 5 / 16
     with pytest.raises(ValueError):
         mxc.int_format(8)
+
+
+def test_bench_names_the_reduce_kernel_by_the_librarys_own_rule():
+    """bench.py reports which reduce kernel a call launches; its rule must be the host
+    dispatch's: same element type, same rank range, same tile size, same size limit."""
+    import bench
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = open(os.path.join(root, "paper_2411_09510_amd", "csrc", "mxc_reduce.hpp")).read()
+    disp = open(os.path.join(root, "paper_2411_09510_amd", "csrc", "mxc_dispatch.hpp")).read()
+    m = re.search(r"kHalfFormMaxUnits = \(size_t\)(\d+) \* (\d+) / 8;", src)
+    max_elems = int(m.group(1)) * int(m.group(2))
+    min_ranks = int(re.search(r"kHalfFormMinRanks = (\d+);", src).group(1))
+    max_ranks = int(re.search(r"kFastRanks = (\d+);", src).group(1))
+    assert "kHalfFormOk = E::hw == HW_FP4" in src                       # E2M1 only
+    assert "a.tp >= kHalfFormMinRanks && a.tp <= kFastRanks && a.units % 128 == 0 && a.units <= kHalfFormMaxUnits" in disp
+    half, tile = "dequant_reduce_half_kernel", "dequant_reduce_tile_kernel"
+    assert bench.reduce_kernel(2, 1, max_ranks, 4096, 8192) == half
+    assert bench.reduce_kernel(2, 1, min_ranks, 1, 1024) == half
+    assert bench.reduce_kernel(2, 1, min_ranks - 1, 4096, 8192) == tile
+    assert bench.reduce_kernel(2, 1, max_ranks + 1, 4096, 8192) == tile
+    assert bench.reduce_kernel(2, 1, max_ranks, max_elems // 8192, 8192) == half
+    assert bench.reduce_kernel(2, 1, max_ranks, max_elems // 8192 + 1, 8192) == tile
+    assert bench.reduce_kernel(2, 1, max_ranks, 3, 1056) == tile            # not whole 1024-element tiles
+    assert bench.reduce_kernel(2, 2, max_ranks, 4096, 8192) == tile
+    assert bench.reduce_kernel(3, 2, max_ranks, 4096, 8192) == tile
