@@ -62,6 +62,9 @@ def parse_args():
     ap.add_argument("--no-sweep", action="store_true", help="skip the untimed sweep")
     ap.add_argument("--no-pipelines", action="store_true",
                     help="skip the requantize pipelines of configurations 4 and 5 in the sweep")
+    ap.add_argument("--one-rank", action="store_true",
+                    help="also time what one rank of the group launches per all-reduce: the quantize of a "
+                         "single partial and the decode of a single compressed copy")
     ap.add_argument("--tp-sweep", action="store_true",
                     help="add the reduce kernel's rate from 1, 2, 4, ... of the partials to the sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -506,16 +509,17 @@ def main():
                 timer.each(lambda i: mxc.dequant_reduce_own(
                     f, i % N, x_sets[i % 2][i % N], ps[i % R][0], ps[i % R][1],
                     out=outs16[i % NOUT16])))
-            # what one rank of the group runs per all-reduce: quantize its own partial (one
-            # [T x H] tensor; the 2 x N inputs rotate, 1 GiB), and, in the reduce-scatter
-            # variant, decode the all-gathered chunks (one compressed copy of the whole tensor)
-            q1 = [mxc.prepare_quantize_batched(f, [x_sets[i % 2][(i // 2) % N]], [ps[i % R][0][(i // 2) % N]],
-                                               [ps[i % R][1][(i // 2) % N]]) for i in range(2 * N * R)]
-            entry["quantize_one_partial"] = rate(T * H * 2 + pk, timer.each(lambda i: q1[i % len(q1)]()))
-            d1 = [mxc.prepare_dequant_reduce(f, [ps[i % R][0][(i // R) % N]], [ps[i % R][1][(i // R) % N]],
-                                             T, H, outs[i % NOUT]) for i in range(N * R * NOUT)]
-            entry["decode_one_copy_f32"] = rate(pk + T * H * 4, timer.each(lambda i: d1[i % len(d1)]()))
-            del q1, d1
+            if args.one_rank:
+                # what one rank of the group runs per all-reduce: quantize its own partial (one
+                # [T x H] tensor; the 2 x N inputs rotate, 1 GiB), and, in the reduce-scatter
+                # variant, decode the all-gathered chunks (one compressed copy of the whole tensor)
+                q1 = [mxc.prepare_quantize_batched(f, [x_sets[i % 2][(i // 2) % N]], [ps[i % R][0][(i // 2) % N]],
+                                                   [ps[i % R][1][(i // 2) % N]]) for i in range(2 * N * R)]
+                entry["quantize_one_partial"] = rate(T * H * 2 + pk, timer.each(lambda i: q1[i % len(q1)]()))
+                d1 = [mxc.prepare_dequant_reduce(f, [ps[i % R][0][(i // R) % N]], [ps[i % R][1][(i // R) % N]],
+                                                 T, H, outs[i % NOUT]) for i in range(N * R * NOUT)]
+                entry["decode_one_copy_f32"] = rate(pk + T * H * 4, timer.each(lambda i: d1[i % len(d1)]()))
+                del q1, d1
             # requantize (extension): every 1/N row chunk of the reduced tensor, one launch per
             # chunk as the ranks would issue them, and the whole tensor in one launch
             rows = T // N
