@@ -519,7 +519,10 @@ def main():
                 d1 = [mxc.prepare_dequant_reduce(f, [ps[i % R][0][(i // R) % N]], [ps[i % R][1][(i // R) % N]],
                                                  T, H, outs[i % NOUT]) for i in range(N * R * NOUT)]
                 entry["decode_one_copy_f32"] = rate(pk + T * H * 4, timer.each(lambda i: d1[i % len(d1)]()))
-                del q1, d1
+                d16 = [mxc.prepare_dequant_reduce(f, [ps[i % R][0][(i // R) % N]], [ps[i % R][1][(i // R) % N]],
+                                                  T, H, outs16[i % NOUT16]) for i in range(N * R * NOUT16)]
+                entry["decode_one_copy_bf16"] = rate(pk + T * H * 2, timer.each(lambda i: d16[i % len(d16)]()))
+                del q1, d1, d16
             # requantize (extension): every 1/N row chunk of the reduced tensor, one launch per
             # chunk as the ranks would issue them, and the whole tensor in one launch
             rows = T // N

@@ -110,11 +110,18 @@ __device__ __forceinline__ void decode_unit_hw(uint64_t v, float hw_scale, float
     d[4] = r2.x; d[5] = r2.y; d[6] = r3.x; d[7] = r3.y;
 }
 
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f)
+// Two binary32 values -> two bfloat16 (a in the low half), round to nearest even, NaN -> 0x7FC0.
+// The conversion is the compiler's (v_cvt_pk_bf16_f32 on gfx950: round to nearest even, bfloat16
+// subnormals kept); it keeps a NaN's sign and payload, so NaN halves, (h & 0x7FFF) > 0x7F80, are
+// replaced afterwards: adding 0x7F carries exactly those into bit 15, and a 24-bit multiply
+// widens the two flag bits into half-word masks.
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2_rne(float a, float b)
 {
-    uint32_t u = __float_as_uint(f);
-    uint32_t r = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-    return (f != f) ? 0x7FC0u : r;
+    const f32x2 v = {a, b};
+    const uint32_t r = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+    const uint32_t t = ((r & 0x7FFF7FFFu) + 0x007F007Fu) & 0x80008000u;
+    const uint32_t m = __umul24(t >> 15, 0xFFFFu);
+    return bitselect(m, 0x7FC07FC0u, r);
 }
 
 // LEN bits starting at bit `pos` of a little-endian stream held in NW dwords.  Callers pass
@@ -436,7 +443,7 @@ __device__ __forceinline__ void store_sums(u32x4 *t, const float (&acc)[32], voi
         if (OUT_BF16) {
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                v[j] = f32_to_bf16_rne(acc[8 * c + 2 * j]) | (f32_to_bf16_rne(acc[8 * c + 2 * j + 1]) << 16);
+                v[j] = f32x2_to_bf16x2_rne(acc[8 * c + 2 * j], acc[8 * c + 2 * j + 1]);
         } else {
 #pragma unroll
             for (int j = 0; j < 4; ++j) v[j] = __float_as_uint(acc[4 * c + j]);
@@ -947,7 +954,7 @@ __device__ __forceinline__ void reduce_wave_half(const ReduceArgs &a, u32x4 *t, 
         if (OUT_BF16) {
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                v[j] = f32_to_bf16_rne(acc[8 * c + 2 * j]) | (f32_to_bf16_rne(acc[8 * c + 2 * j + 1]) << 16);
+                v[j] = f32x2_to_bf16x2_rne(acc[8 * c + 2 * j], acc[8 * c + 2 * j + 1]);
         } else {
 #pragma unroll
             for (int j = 0; j < 4; ++j) v[j] = __float_as_uint(acc[4 * c + j]);
