@@ -445,6 +445,42 @@ def test_reduce_e2m1_tensors_of_whole_kilo_element_tiles(mxc, oracle_mod, B, s):
                                   oracle_mod.round_to_bf16(want)), (tp, own)
 
 
+def test_bf16_output_rounding_at_every_bf16_value(mxc, oracle_mod):
+    """Rounding of the binary32 sum to a bf16 output, at its hardest inputs: the own partial holds
+    every bf16 bit pattern (65 536 elements: both signs, subnormals, Inf, NaN) and the one other
+    rank adds a quarter, a half or three quarters of that element's bf16 unit in the last place
+    (E2M1 codes 0.5, 1.0, 1.5 under a per-block scale of 2^(exponent - 8)), so that the sum lies
+    below, exactly on and above the midpoint between two bf16 values for every one of them."""
+    fo, fg = oracle_mod.Format(2, 1, 32, 8), mxc.Format(2, 1, 32, 8)
+    T, H = 64, 1024                                   # 65 536 elements, whole 1024-element tiles
+    own_bits = np.arange(65536, dtype=np.uint16).reshape(T, H)
+    expfield = ((own_bits >> 7) & 0xFF).reshape(T, H // 32, 32)[:, :, 0].astype(np.int32)
+    scale = np.clip(expfield - 8, 0, 254).astype(np.uint8)    # a block of 32 patterns shares its exponent
+    for code in (1, 2, 3, 9, 10, 11):                 # +-0.5, +-1.0, +-1.5 times the scale
+        other = np.full((T, H), code, np.uint8)
+        for tp, own in ((2, 0), (2, 1), (7, 3)):      # the general and the 1024-element-tile forms
+            cs = [np.zeros((T, H), np.uint8) for _ in range(tp)]
+            ss = [np.full((T, H // 32), 127, np.uint8) for _ in range(tp)]
+            k = (own + 1) % tp
+            cs[k], ss[k] = other, scale
+            packed = [torch.from_numpy(oracle_mod.pack(fo, c)).cuda() for c in cs]
+            scales = [torch.from_numpy(v).cuda() for v in ss]
+            got16 = mxc.dequant_reduce_own(fg, own, dev_bf16(own_bits), packed, scales, out_dtype=torch.bfloat16)
+            got32 = mxc.dequant_reduce_own(fg, own, dev_bf16(own_bits), packed, scales)
+            torch.cuda.synchronize()
+            want = oracle_mod.dequant_reduce_own(fo, own, own_bits, cs, ss)
+            assert same_f32(host(got32), want), (code, tp, own)
+            assert np.array_equal(host(got16.view(torch.int16)).view(np.uint16),
+                                  oracle_mod.round_to_bf16(want)), (code, tp, own)
+    # the midpoints really are among the sums: with +1.0 x scale the float32 sum of a positive
+    # normal value has exactly the bit below bf16's last place set
+    cs = [np.zeros((T, H), np.uint8), np.full((T, H), 2, np.uint8)]
+    ss = [np.full((T, H // 32), 127, np.uint8), scale]
+    s32 = oracle_mod.dequant_reduce_own(fo, 0, own_bits, cs, ss).view(np.uint32)
+    pos_normal = (own_bits >= (9 << 7)) & (own_bits < (0xFF << 7))
+    assert np.all((s32[pos_normal] & 0xFFFF) == 0x8000)
+
+
 # ------------------------------------------------------------------------ requantize --------
 
 @pytest.mark.parametrize("x,y,B", [(2, 1, 16), (2, 1, 32), (2, 2, 32), (3, 2, 32), (1, 3, 8)])
