@@ -57,6 +57,12 @@ struct Elem {
                                                                                        : HW_NONE;
     // exponent bias of that hardware format
     static constexpr int hw_bias = hw == HW_BF8 ? 15 : hw == HW_FP8 ? 7 : beta;
+    // Decoding only: a format with one mantissa bit is also part of BF8's code space once its
+    // mantissa is padded with a zero bit (same values; not usable for rounding, which would
+    // round twice).  dec_pad: zero bits to append to the magnitude.
+    static constexpr int dec_pad = (hw == HW_NONE && Y == 1) ? 1 : 0;
+    static constexpr int hw_dec = dec_pad ? HW_BF8 : hw;
+    static constexpr int hw_dec_bias = dec_pad ? 15 : hw_bias;
 };
 
 // Scale format EsM0, runtime (s only changes two clamps per block).

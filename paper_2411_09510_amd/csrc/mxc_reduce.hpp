@@ -56,7 +56,7 @@ __device__ __forceinline__ uint32_t bitselect(uint32_t m, uint32_t a, uint32_t b
 }
 
 // Four b-bit codes in the low 4b bits of f (bits above are ignored) -> four bytes
-// sign<<7 | magnitude.
+// sign<<7 | magnitude << E::dec_pad (the byte the format's hardware decode format expects).
 //
 // General form: copy k of f, shifted left by k*(8-b), carries code k's magnitude at byte k and
 // code k-1's sign at bit 7 of byte k-1; four selects stitch the copies together and one mask
@@ -77,14 +77,18 @@ __device__ __forceinline__ uint32_t codes_to_bytes(uint32_t f)
         // bytes 0 and 2 of `even`, bytes 1 and 3 of `odd`: code k in bits 0-4 of byte k (a byte
         // permute, which the compiler keeps as one instruction; an and/or select it splits up)
         const uint32_t c5 = __builtin_amdgcn_perm(odd, even, 0x07020500u);
-        return (c5 & 0x0F0F0F0Fu) | ((c5 << 3) & 0x80808080u);
+        // (a one-mantissa-bit format's magnitude moves up by its pad bit: see below)
+        return ((c5 & 0x0F0F0F0Fu) << E::dec_pad) | ((c5 << 3) & 0x80808080u);
     }
     uint32_t r = f;
     r = bitselect((1u << (b - 1)) - 1u, r, f << g);
     r = bitselect((1u << (8 + b - 1)) - 1u, r, f << (2 * g));
     r = bitselect((1u << (16 + b - 1)) - 1u, r, f << (3 * g));
     r = bitselect((1u << (24 + b - 1)) - 1u, r, f << (4 * g));
-    return r & ((E::magmask | 0x80u) * 0x01010101u);
+    r &= (E::magmask | 0x80u) * 0x01010101u;
+    // one-mantissa-bit formats: the magnitude moves up by the pad bit, the sign stays
+    if (E::dec_pad) r = (r & 0x80808080u) | ((r & 0x7F7F7F7Fu) << E::dec_pad);
+    return r;
 }
 
 // Eight codes -> eight binary32 values times the power of two in hw_scale's exponent field.
@@ -92,13 +96,13 @@ template <class E>
 __device__ __forceinline__ void decode_unit_hw(uint64_t v, float hw_scale, float (&d)[8])
 {
     f32x2 r0, r1, r2, r3;
-    if (E::hw == HW_FP4) {
+    if (E::hw_dec == HW_FP4) {
         r0 = cvt_fp4_pair<0>((uint32_t)v, hw_scale);
         r1 = cvt_fp4_pair<1>((uint32_t)v, hw_scale);
         r2 = cvt_fp4_pair<2>((uint32_t)v, hw_scale);
         r3 = cvt_fp4_pair<3>((uint32_t)v, hw_scale);
     } else {
-        constexpr int K = E::hw == HW_BF8 ? HW_BF8 : HW_FP8;
+        constexpr int K = E::hw_dec == HW_BF8 ? HW_BF8 : HW_FP8;
         const uint32_t b0 = codes_to_bytes<E>((uint32_t)v);
         const uint32_t b1 = codes_to_bytes<E>((uint32_t)(v >> (4 * E::bits)));
         r0 = cvt_8bit_pair<K, false>(b0, hw_scale);
@@ -302,7 +306,7 @@ __device__ __forceinline__ void add_chunk(const ChunkBits<E::bits> &c, const Sca
                                           bool (&poisoned)[32 / B])
 {
     constexpr int W = E::bits, NB = 32 / B;
-    constexpr bool kHw = HW && E::hw != HW_NONE;
+    constexpr bool kHw = HW && E::hw_dec != HW_NONE;
     // the chunk is one block of a hardware 6-bit format: BF6 = E3M2; FP6 = E2M3, of which E2M2
     // is the half with an even mantissa (same bias, same largest exponent: 6-bit code = 5-bit
     // code << 1)
@@ -314,7 +318,7 @@ __device__ __forceinline__ void add_chunk(const ChunkBits<E::bits> &c, const Sca
         const int sc = (int)((c.sw >> (8 * n)) & 0xFFu);
         const int e = sc - sf.sbias;
         poisoned[n] = poisoned[n] || (sf.has_nan && sc == 255);
-        const int field = kChunk6 ? e + 127 : e - E::beta + E::hw_bias + 127;
+        const int field = kChunk6 ? e + 127 : e - E::beta + E::hw_dec_bias + 127;
         const bool ok = field >= 0 && field <= 254;
         float d[B];
         if (kHw && kChunk6 && __builtin_amdgcn_ballot_w64(!ok) == 0) {
