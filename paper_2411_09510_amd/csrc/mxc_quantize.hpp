@@ -38,6 +38,33 @@ __device__ __forceinline__ uint64_t encode_unit_generic(const u32x4 (&w)[SRC32 ?
     return packed;
 }
 
+// Eight elements -> packed codes for a one-bit exponent (E1My, the INT grids of the Method list):
+// the magnitudes are the uniform grid 0, step, 2 step, ... with step = 2^(1-y), so the code is
+// round-half-even(|v| * 2^-e / step), saturated; one multiply by a power of two (exact, or
+// so far below half a step that it rounds to zero either way), one round, one clamp.
+// inv_step = 2^(-e - 1 + y).
+template <class E, bool SRC32>
+__device__ __forceinline__ uint64_t encode_unit_uniform(const u32x4 (&w)[SRC32 ? 2 : 1], float inv_step)
+{
+    static_assert(E::x == 1, "uniform grid: one exponent bit");
+    uint64_t packed = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        uint32_t bits;
+        if (SRC32) {
+            bits = w[j >> 2][j & 3];
+        } else {
+            const uint32_t pair = w[0][j >> 1];
+            bits = (j & 1) ? (pair & 0xFFFF0000u) : (pair << 16);
+        }
+        const float q = __builtin_fminf(__builtin_rintf(__builtin_fabsf(__uint_as_float(bits)) * inv_step),
+                                        (float)E::magmask);
+        const uint32_t code = (uint32_t)q | ((bits >> 31) << (E::x + E::y));
+        packed |= (uint64_t)code << (j * E::bits);
+    }
+    return packed;
+}
+
 // Scaled conversions need their byte / word selector as a literal: one wrapper per selector.
 template <int K, bool SRC32, int NW>
 __device__ __forceinline__ uint32_t cvt_pair_to_fp4(uint32_t old, const u32x4 (&w)[NW], float s)
@@ -120,7 +147,7 @@ __device__ __forceinline__ uint64_t encode_unit(const u32x4 (&w)[SRC32 ? 2 : 1],
     *scale_byte = sc;
 
     uint64_t packed;
-    if (kHw) {
+    if constexpr (kHw) {
         // divide by 2^(e - beta + hw_bias): the element format's smallest normal then falls on
         // the hardware format's smallest normal.  Usable while that power of two has a binary32
         // exponent field and (for the 8-bit formats) the scale's upper clamp is idle, which is
@@ -129,6 +156,15 @@ __device__ __forceinline__ uint64_t encode_unit(const u32x4 (&w)[SRC32 ? 2 : 1],
         const bool ok = field >= 0 && field <= 254 && (E::hw == HW_FP4 || unclamped <= sf.smax);
         if (__builtin_amdgcn_ballot_w64(!ok && finite) == 0) {
             packed = encode_unit_hw<E, SRC32>(w, __uint_as_float((uint32_t)max(field, 0) << 23));
+        } else {
+            packed = encode_unit_generic<E, SRC32>(w, -e);
+        }
+    } else if constexpr (E::x == 1) {
+        // 2^(-e - 1 + y) as a binary32: its exponent field is in range for every scale a finite
+        // block can have (e <= 126), checked all the same
+        const int field = -e - 1 + E::y + 127;
+        if (__builtin_amdgcn_ballot_w64((field < 1 || field > 254) && finite) == 0) {
+            packed = encode_unit_uniform<E, SRC32>(w, __uint_as_float((uint32_t)min(max(field, 1), 254) << 23));
         } else {
             packed = encode_unit_generic<E, SRC32>(w, -e);
         }
