@@ -62,6 +62,9 @@ def parse_args():
     ap.add_argument("--no-sweep", action="store_true", help="skip the untimed sweep")
     ap.add_argument("--no-pipelines", action="store_true",
                     help="skip the requantize pipelines of configurations 4 and 5 in the sweep")
+    ap.add_argument("--format-table", action="store_true",
+                    help="also time quantize and dequant-reduce for every element type of the Method list "
+                         "(blocks of 32 and 8)")
     ap.add_argument("--one-rank", action="store_true",
                     help="also time what one rank of the group launches per all-reduce: the quantize of a "
                          "single partial and the decode of a single compressed copy")
@@ -166,6 +169,33 @@ def quality_table(mxc, torch, xs, T, H):
                 table[f"e{fx}m{fy}_b{fb}_s{fs}"] = {
                     "effective_bits": mxc.effective_bits(f), "sqnr_db": sqnr_db(torch, out, exact)}
                 del codes, scales
+    return table
+
+
+def format_table(mxc, torch, timer, x_sets, outs, T, H, N):
+    """Kernel times of quantize (all N partials) and dequant-reduce (to float32) over the
+    element types of the Method list and two block sizes, on the timed workload's tensors; packed
+    sets laid out and rotated as in the timed step."""
+    table = {}
+    for (fx, fy) in [(1, 1), (1, 2), (2, 1), (1, 3), (2, 2), (3, 1), (1, 4), (2, 3), (3, 2)]:
+        for fb in (32, 8):
+            f = mxc.Format(fx, fy, fb, 8)
+            cb, sb = mxc.packed_sizes(f, T, H)
+            sets = []
+            for _ in range(3):
+                buf = torch.empty(N * (cb + sb), dtype=torch.uint8, device="cuda")
+                sets.append(([buf[r * (cb + sb): r * (cb + sb) + cb].view(T, cb // T) for r in range(N)],
+                             [buf[r * (cb + sb) + cb: (r + 1) * (cb + sb)].view(T, sb // T) for r in range(N)]))
+                mxc.quantize_batched(f, x_sets[0], *sets[-1])
+            ql = [mxc.prepare_quantize_batched(f, x_sets[k % 2], *sets[k % 3]) for k in range(6)]
+            dl = [mxc.prepare_dequant_reduce(f, *sets[k % 3], T, H, outs[k % len(outs)])
+                  for k in range(3 * len(outs))]
+            table[f"e{fx}m{fy}_b{fb}"] = {
+                "effective_bits": mxc.effective_bits(f),
+                "quantize": rate(N * (T * H * 2 + cb + sb), timer.each(lambda i: ql[i % len(ql)]())),
+                "dequant_reduce": rate(N * (cb + sb) + T * H * 4, timer.each(lambda i: dl[i % len(dl)]())),
+            }
+            del sets, ql, dl
     return table
 
 
@@ -643,6 +673,8 @@ def main():
 
     if args.quality_table:
         result["quality_table"] = quality_table(mxc, torch, x_sets[0], T, H)
+    if args.format_table:
+        result["format_table"] = format_table(mxc, torch, timer, x_sets, outs, T, H, N)
 
     # ---- the requantize pipelines of the two larger configurations (default workload only) --
     if not args.no_sweep and not args.no_pipelines and args.config == 3:
